@@ -1,0 +1,209 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Loads ``nvfp4_oracle.c`` (built with gcc into ``oracle/libnvfp4_oracle.so``) through
+ctypes and composes its primitives into the quantizers and the three matrix
+products of the NVFP4 linear layer (TetraJet-v2, Sec. 2.1-2.3).  Only tests/, the
+smoke check and the bench's ``cpu_baseline`` leg may import this package; it does
+not import the GPU package and the GPU package does not import it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nvfp4_oracle.c")
+_SO = os.path.join(_HERE, "libnvfp4_oracle.so")
+
+RTN, SR = 0, 1
+SCALE_DEFAULT, SCALE_NE, SCALE_UP = 0, 1, 2
+OUTER_TENSOR, OUTER_BLOCK128 = 0, 1
+
+FP4_VALUES = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-shared", "-fPIC", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        p, i64, i32, u64, u32, f32 = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_uint32, C.c_float
+        L.oracle_e4m3_value.restype = f32
+        L.oracle_e4m3_value.argtypes = [C.c_uint8]
+        L.oracle_e4m3_round.restype = C.c_uint8
+        L.oracle_e4m3_round.argtypes = [f32, i32]
+        L.oracle_stream_key.restype = u64
+        L.oracle_stream_key.argtypes = [u64, u32]
+        L.oracle_pair_bits.restype = u32
+        L.oracle_pair_bits.argtypes = [u32, u64]
+        L.oracle_rand16.restype = u32
+        L.oracle_rand16.argtypes = [u64, u64]
+        L.oracle_round_rtn.restype = i32
+        L.oracle_round_rtn.argtypes = [f32]
+        L.oracle_round_sr.restype = i32
+        L.oracle_round_sr.argtypes = [f32, u32]
+        L.oracle_global_scale.restype = f32
+        L.oracle_global_scale.argtypes = [f32]
+        L.oracle_quantize_rows.restype = i32
+        L.oracle_quantize_rows.argtypes = [p, i64, i64, i32, i32, i32, u64, u32, p, p, p, p]
+        L.oracle_dequant_f32.restype = i32
+        L.oracle_dequant_f32.argtypes = [p, p, p, i64, i64, i32, p]
+        L.oracle_dequant_f64.restype = i32
+        L.oracle_dequant_f64.argtypes = [p, p, p, i64, i64, i32, p]
+        L.oracle_gemm_nt_f64.restype = i32
+        L.oracle_gemm_nt_f64.argtypes = [p, p, i64, i64, i64, p, p]
+        L.oracle_bf16_to_f32.restype = None
+        L.oracle_bf16_to_f32.argtypes = [p, i64, p]
+        L.oracle_transpose_f32.restype = None
+        L.oracle_transpose_f32.argtypes = [p, i64, i64, p]
+        L.oracle_abs_max_f32.restype = f32
+        L.oracle_abs_max_f32.argtypes = [p, i64]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class NVFP4:
+    """One quantized operand, K contiguous: codes [rows, K/2], scales [rows, K/16]."""
+    codes: np.ndarray
+    scales: np.ndarray
+    gscale: np.ndarray          # [1] (TENSOR) or [rows, K/128] (BLOCK128)
+    amax_deq: float
+    rows: int
+    K: int
+    outer: int
+
+
+def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float32)
+    lib().oracle_bf16_to_f32(_ptr(bits), bits.size, _ptr(out))
+    return out
+
+
+def transpose_f32(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    R, Cc = x.shape
+    out = np.empty((Cc, R), dtype=np.float32)
+    lib().oracle_transpose_f32(_ptr(x), R, Cc, _ptr(out))
+    return out
+
+
+def quantize_f32(x: np.ndarray, rounding: int, scale_round: int = SCALE_DEFAULT,
+                 outer: int = OUTER_TENSOR, seed: int = 0, tensor_id: int = 0) -> NVFP4:
+    """Quantize a float32 [rows, K] view along K (Sec. 2.2)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, K = x.shape
+    codes = np.zeros((rows, K // 2), dtype=np.uint8)
+    scales = np.zeros((rows, K // 16), dtype=np.uint8)
+    gscale = np.zeros((1,) if outer == OUTER_TENSOR else (rows, K // 128), dtype=np.float32)
+    amax_deq = C.c_float(0.0)
+    rc = lib().oracle_quantize_rows(_ptr(x), rows, K, rounding, scale_round, outer,
+                                    seed, tensor_id, _ptr(codes), _ptr(scales), _ptr(gscale),
+                                    C.cast(C.byref(amax_deq), C.c_void_p))
+    if rc != 0:
+        raise ValueError("oracle_quantize_rows: bad shape or enum")
+    return NVFP4(codes, scales, gscale, float(amax_deq.value), rows, K, outer)
+
+
+def quantize_bf16(src_bits: np.ndarray, axis: int, rounding: int, **kw) -> NVFP4:
+    """Quantize a bf16 [R, C] tensor row-wise (axis=0: K=C) or column-wise
+    (axis=1: K=R, the result describes the transpose [C, R]); Sec. 2.3 group shapes."""
+    x = bf16_to_f32(src_bits)
+    if axis == 1:
+        x = transpose_f32(x)
+    return quantize_f32(x, rounding, **kw)
+
+
+def dequant_f32(q: NVFP4) -> np.ndarray:
+    out = np.empty((q.rows, q.K), dtype=np.float32)
+    rc = lib().oracle_dequant_f32(_ptr(q.codes), _ptr(q.scales), _ptr(q.gscale), q.rows, q.K, q.outer, _ptr(out))
+    assert rc == 0
+    return out
+
+
+def dequant_f64(q: NVFP4, rows=None) -> np.ndarray:
+    """Exact dequantized values; ``rows`` optionally selects a subset of rows."""
+    if rows is not None:
+        rows = np.asarray(rows)
+        gs = q.gscale if q.outer == OUTER_TENSOR else np.ascontiguousarray(q.gscale[rows])
+        q = NVFP4(np.ascontiguousarray(q.codes[rows]), np.ascontiguousarray(q.scales[rows]), gs,
+                  q.amax_deq, len(rows), q.K, q.outer)
+    out = np.empty((q.rows, q.K), dtype=np.float64)
+    rc = lib().oracle_dequant_f64(_ptr(q.codes), _ptr(q.scales), _ptr(q.gscale), q.rows, q.K, q.outer, _ptr(out))
+    assert rc == 0
+    return out
+
+
+def requantize(q: NVFP4, axis: int, rounding: int, **kw) -> NVFP4:
+    """Quantize an NVFP4 tensor again (Q4 / Q6 of Sec. 2.3) from its binary32 dequantized value."""
+    x = dequant_f32(q)
+    if axis == 1:
+        x = transpose_f32(x)
+    return quantize_f32(x, rounding, **kw)
+
+
+def gemm_nt_f64(A: np.ndarray, B: np.ndarray):
+    """C = A @ B.T in binary64 with sequential k; also returns sum_k |a||b|."""
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    B = np.ascontiguousarray(B, dtype=np.float64)
+    M, K = A.shape
+    N, K2 = B.shape
+    assert K == K2
+    Cm = np.empty((M, N), dtype=np.float64)
+    Ab = np.empty((M, N), dtype=np.float64)
+    lib().oracle_gemm_nt_f64(_ptr(A), _ptr(B), M, N, K, _ptr(Cm), _ptr(Ab))
+    return Cm, Ab
+
+
+def gemm_nt(qa: NVFP4, qb: NVFP4, rows_a=None, rows_b=None):
+    """Quantized NT product of two operands (optionally on sampled rows of A and / or B)."""
+    assert qa.K == qb.K
+    return gemm_nt_f64(dequant_f64(qa, rows_a), dequant_f64(qb, rows_b))
+
+
+def tensor_id(layer_id: int, quantizer_index: int) -> int:
+    """Stream id of quantizer Q^(k) of a layer (k = 1..6 as numbered in Sec. 2.3)."""
+    return layer_id * 8 + quantizer_index
+
+
+# ----- the linear layer of Sec. 2.3 ------------------------------------------------------
+
+def linear_fwd(X_bits, W_bits, outer: int = OUTER_TENSOR):
+    """Y = Q1_D(X) x Q2_D(W^T): returns (Xq, Wq); both are grouped along D."""
+    Xq = quantize_bf16(X_bits, 0, RTN, outer=outer)
+    Wq = quantize_bf16(W_bits, 0, RTN, outer=outer)
+    return Xq, Wq
+
+
+def linear_bwd_dx_operands(dY_bits, Wq: NVFP4, seed: int, layer_id: int, outer: int = OUTER_TENSOR):
+    """dX = Q3_S(dY) x Q4_S(W_hat): returns (dYq [N, C], Wq' [D, C]), both grouped along C."""
+    dYq = quantize_bf16(dY_bits, 0, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 3))
+    Wq2 = requantize(Wq, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 4))
+    return dYq, Wq2
+
+
+def linear_bwd_dw_operands(dY_bits, Xq: NVFP4, seed: int, layer_id: int, outer: int = OUTER_TENSOR):
+    """dW = Q5_S(dY^T) x Q6_S(X_hat): returns (dYq' [C, N], Xq' [D, N]), both grouped along N."""
+    dYq = quantize_bf16(dY_bits, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 5))
+    Xq2 = requantize(Xq, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 6))
+    return dYq, Xq2

@@ -1,0 +1,337 @@
+/*
+ * CPU oracle for the NVFP4 double-block quantizer and the quantized GEMM.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the GPU
+ * library is checked against.  It shares no code, table or header with the HIP
+ * path, and nothing in the product path may call it: only tests/, the smoke
+ * check and the bench's cpu_baseline leg load it.
+ *
+ * What it follows (TetraJet-v2, arXiv 2510.27527):
+ *   - E2M1 value set {0, +-0.5, 1, 1.5, 2, 3, 4, 6}          Sec. 2.1 "NVFP4 Format"
+ *   - group quantization P_i = round_FP4(X_i / S)             Sec. 2.1 "Quantization"
+ *   - deterministic rounding = nearest FP4 value              Sec. 2.1, round_{FP4,D}
+ *   - stochastic rounding between neighbours q1 <= x < q2     Sec. 2.1, round_{FP4,S}
+ *   - double-block scaling S_global, S_block                  Sec. 2.2 (display eq.)
+ *   - the six quantizers / three matrix products              Sec. 2.3 (display eq.)
+ *
+ * Where the paper leaves the arithmetic open, this file takes the readings
+ * listed here (the same list is in the design document):
+ *   R1  All quantizer arithmetic that decides a code is IEEE binary32,
+ *       round-to-nearest-even, one rounding per written operation, no fused
+ *       multiply-add, subnormals kept.  Order:  S_g = amax_g / 2688 ;
+ *       c_g = 6 * S_g ; s = amax_b / c_g ; S_b = e4m3(s) ; d = S_g * S_b ;
+ *       r = 1 / d ; y = x * r ; a = min(|y|, 6).
+ *   R2  S_g is floored at 2^-100 (keeps 1/d finite); an all-zero outer group
+ *       gets S_g = 1 and all-zero scales and codes.
+ *   R3  The block scale is rounded to E4M3 (bias 7, no infinity, max 448,
+ *       subnormals k * 2^-9) either to nearest-even (SCALE_NE) or upward
+ *       (SCALE_UP); both saturate at 448.  Default: NE for deterministic
+ *       rounding, UP for stochastic rounding (a scale rounded down would clip
+ *       the block maximum and bias the estimate).
+ *   R4  Deterministic rounding breaks ties toward the even code.
+ *   R5  Stochastic rounding: the paper's xi ~ U(-D/2, D/2) with D = q2 - q1 and
+ *       "x + xi <= midpoint -> q1" is taken on a discrete uniform of 16 bits:
+ *       with f = (a - q1)/D and L = floor(f * 2^16), a is rounded up iff
+ *       u + L >= 2^16 for u uniform on {0..65535}; so P(q2) = L / 2^16.  Below
+ *       1 (the E2M1 subnormal range) a is first rounded to a multiple of 2^-23.
+ *   R6  The random 16 bits of output element e (index in the quantized
+ *       operand's own [rows x K] view) come from a counter-based hash of the
+ *       pair index e>>1, keyed by (seed, tensor id); see rand16() below.
+ *   R7  A code is sign<<3 | index into the ascending value set; -0 is never
+ *       emitted.  Element k of a row sits in byte k/2, even k in the low nibble.
+ *   R8  Re-quantizing an NVFP4 tensor (Q4, Q6 of Sec. 2.3) starts from its
+ *       binary32 dequantized value  x = RN( (P * S_b) * S_g ).
+ *
+ * Parity status: R1, R6, R7 are not fixed by the paper ("parity unpinned" by
+ * the paper itself); they are pinned by the property tests in tests/ (grid
+ * membership, exact round trips, scale/absmax invariants, closed-form SR
+ * probabilities, unbiasedness, brute-force GEMMs).
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#if defined(__FAST_MATH__)
+#error "the oracle must be built without -ffast-math"
+#endif
+
+enum { ROUND_RTN = 0, ROUND_SR = 1 };
+enum { SCALE_DEFAULT = 0, SCALE_NE = 1, SCALE_UP = 2 };
+enum { OUTER_TENSOR = 0, OUTER_BLOCK128 = 1 };
+
+/* Sec. 2.1: FP4Values, non-negative half in ascending order. */
+static const float FP4_VALUES[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+
+/* ------------------------------------------------------------------ E4M3 -- */
+
+/* value of a non-negative E4M3 code (0x00..0x7E); R3 */
+float oracle_e4m3_value(uint8_t code)
+{
+    int e = (code >> 3) & 0xF, m = code & 7;
+    if (e == 0) return ldexpf((float)m, -9);
+    return ldexpf(1.0f + (float)m / 8.0f, e - 7);
+}
+
+/* round a non-negative binary32 to an E4M3 code; R3 */
+uint8_t oracle_e4m3_round(float s, int mode)
+{
+    if (!(s > 0.0f)) return 0;
+    if (s >= 448.0f) return 0x7E;
+    /* lo = largest code whose value is <= s */
+    int lo = 0;
+    for (int c = 1; c <= 0x7E; ++c)
+        if (oracle_e4m3_value((uint8_t)c) <= s) lo = c;
+    if (oracle_e4m3_value((uint8_t)lo) == s) return (uint8_t)lo;
+    int hi = lo + 1;
+    if (mode == SCALE_UP) return (uint8_t)hi;
+    double dl = (double)s - (double)oracle_e4m3_value((uint8_t)lo);
+    double dh = (double)oracle_e4m3_value((uint8_t)hi) - (double)s;
+    if (dl < dh) return (uint8_t)lo;
+    if (dh < dl) return (uint8_t)hi;
+    return (uint8_t)((lo & 1) ? hi : lo);
+}
+
+/* ------------------------------------------------------------------- RNG -- */
+
+static uint64_t mix64(uint64_t z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+/* R6: the 64-bit stream key of (seed, tensor id) */
+uint64_t oracle_stream_key(uint64_t seed, uint32_t tensor_id)
+{
+    uint64_t a = mix64(seed + 0x9E3779B97F4A7C15ull);
+    uint64_t b = ((uint64_t)tensor_id + 1ull) * 0xD1B54A32D192ED03ull;
+    return mix64(a ^ b);
+}
+
+/* R6: 32 random bits of pair p under key (k0 = low word, k1 = high word) */
+uint32_t oracle_pair_bits(uint32_t p, uint64_t key)
+{
+    uint32_t k0 = (uint32_t)key, k1 = (uint32_t)(key >> 32);
+    uint32_t h = p + k0;
+    h ^= h >> 16; h *= 0x7FEB352Du;
+    h ^= h >> 15; h ^= k1; h *= 0x846CA68Bu;
+    h ^= h >> 16;
+    return h;
+}
+
+/* R6: 16 random bits of element e */
+uint32_t oracle_rand16(uint64_t e, uint64_t key)
+{
+    uint32_t h = oracle_pair_bits((uint32_t)(e >> 1), key);
+    return (e & 1) ? (h >> 16) : (h & 0xFFFFu);
+}
+
+/* -------------------------------------------------------------- rounding -- */
+
+/* Sec. 2.1 round_{FP4,D}: index of the nearest FP4 value to a in [0,6]; ties to even index (R4) */
+int oracle_round_rtn(float a)
+{
+    int best = 0;
+    double bd = fabs((double)a - (double)FP4_VALUES[0]);
+    for (int i = 1; i < 8; ++i) {
+        double d = fabs((double)a - (double)FP4_VALUES[i]);
+        if (d < bd || (d == bd && (i % 2 == 0))) { best = i; bd = d; }
+    }
+    return best;
+}
+
+/* Sec. 2.1 round_{FP4,S} with the discrete uniform of R5; u16 in [0, 65536) */
+int oracle_round_sr(float a, uint32_t u16)
+{
+    if (a < 1.0f) a = rintf(a * 8388608.0f) * (1.0f / 8388608.0f);   /* R5: 2^-23 grid below 1 */
+    if (a >= 6.0f) return 7;
+    int i1 = 0;
+    for (int i = 0; i < 7; ++i)
+        if (FP4_VALUES[i] <= a) i1 = i;                               /* q1 <= a < q2 */
+    float q1 = FP4_VALUES[i1], q2 = FP4_VALUES[i1 + 1];
+    double f = ((double)a - (double)q1) / ((double)q2 - (double)q1);
+    uint32_t L = (uint32_t)floor(f * 65536.0);
+    return (u16 + L >= 65536u) ? i1 + 1 : i1;
+}
+
+/* ------------------------------------------------------------- quantizer -- */
+
+static float abs_max(const float *x, int64_t n)
+{
+    float m = 0.0f;
+    for (int64_t i = 0; i < n; ++i) { float v = fabsf(x[i]); if (v > m) m = v; }
+    return m;
+}
+
+/* Sec. 2.2: S_global of an outer group with absolute maximum amax (R1, R2) */
+float oracle_global_scale(float amax)
+{
+    if (amax == 0.0f) return 1.0f;
+    volatile float q = amax / 2688.0f;                 /* 448 * 6 */
+    float floor_ = ldexpf(1.0f, -100);
+    return q > floor_ ? q : floor_;
+}
+
+/*
+ * Quantize x, viewed as [rows x K] with K the grouped (contiguous) axis.
+ *   codes  [rows][K/2], scales [rows][K/16],
+ *   gscale [1] (TENSOR) or [rows][K/128] (BLOCK128),
+ *   amax_deq (optional, [1]): max |binary32 dequantized value| of the result.
+ * Returns 0, or -1 on a bad shape / enum.
+ */
+int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
+                         int rounding, int scale_round, int outer_mode,
+                         uint64_t seed, uint32_t tensor_id,
+                         uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq)
+{
+    if (rows < 0 || K < 0 || K % 16) return -1;
+    if (outer_mode == OUTER_BLOCK128 && K % 128) return -1;
+    if (outer_mode != OUTER_TENSOR && outer_mode != OUTER_BLOCK128) return -1;
+    if (rounding != ROUND_RTN && rounding != ROUND_SR) return -1;
+    if (scale_round == SCALE_DEFAULT) scale_round = rounding == ROUND_RTN ? SCALE_NE : SCALE_UP;
+    if (scale_round != SCALE_NE && scale_round != SCALE_UP) return -1;
+    if ((double)rows * (double)K > 8589934592.0) return -1;        /* pair index must fit 32 bits */
+
+    const uint64_t key = oracle_stream_key(seed, tensor_id);
+    const int64_t outer_len = outer_mode == OUTER_TENSOR ? K : 128;
+    const int64_t outer_per_row = outer_mode == OUTER_TENSOR ? 1 : K / 128;
+
+    float tensor_sg = 1.0f;
+    if (outer_mode == OUTER_TENSOR) {
+        float amax = 0.0f;
+        for (int64_t r = 0; r < rows; ++r) { float m = abs_max(x + r * K, K); if (m > amax) amax = m; }
+        tensor_sg = oracle_global_scale(amax);
+        gscale[0] = tensor_sg;
+    }
+
+    float deq_max = 0.0f;
+#pragma omp parallel for schedule(static) reduction(max : deq_max)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *xr = x + r * K;
+        for (int64_t g = 0; g < outer_per_row; ++g) {
+            float S_g = tensor_sg;
+            if (outer_mode == OUTER_BLOCK128) {
+                S_g = oracle_global_scale(abs_max(xr + g * 128, 128));
+                gscale[r * outer_per_row + g] = S_g;
+            }
+            volatile float c_g = 6.0f * S_g;
+            for (int64_t b = g * outer_len / 16; b < (g + 1) * outer_len / 16; ++b) {
+                const float *xb = xr + b * 16;
+                float amax_b = abs_max(xb, 16);
+                volatile float s = amax_b / c_g;                       /* Sec. 2.2, S_block */
+                uint8_t sc = oracle_e4m3_round(s, scale_round);
+                scales[r * (K / 16) + b] = sc;
+                float S_b = oracle_e4m3_value(sc);
+                volatile float d = S_g * S_b;
+                volatile float rcp = sc == 0 ? 0.0f : 1.0f / d;
+                for (int i = 0; i < 16; ++i) {
+                    int64_t k = b * 16 + i;
+                    volatile float y = xb[i] * rcp;                    /* Sec. 2.2, argument of round_FP4 */
+                    float a = fabsf(y); if (a > 6.0f) a = 6.0f;
+                    int m;
+                    if (rounding == ROUND_RTN) m = oracle_round_rtn(a);
+                    else m = oracle_round_sr(a, oracle_rand16((uint64_t)(r * K + k), key));
+                    int neg = signbit(xb[i]) && m != 0;
+                    uint8_t nib = (uint8_t)((neg << 3) | m);
+                    uint8_t *byte = codes + r * (K / 2) + k / 2;
+                    if (k & 1) *byte = (uint8_t)((*byte & 0x0F) | (nib << 4));
+                    else       *byte = (uint8_t)((*byte & 0xF0) | nib);
+                    volatile float pv = FP4_VALUES[m] * S_b;           /* exact */
+                    volatile float dq = pv * S_g;
+                    if (dq > deq_max) deq_max = dq;
+                }
+            }
+        }
+    }
+    if (amax_deq) *amax_deq = deq_max;
+    return 0;
+}
+
+/* ----------------------------------------------------------- dequantizers -- */
+
+static float code_value(uint8_t nib)
+{
+    float v = FP4_VALUES[nib & 7];
+    return (nib & 8) ? -v : v;
+}
+
+/* R8: binary32 dequantized value RN((P*S_b)*S_g), layout [rows][K] */
+int oracle_dequant_f32(const uint8_t *codes, const uint8_t *scales, const float *gscale,
+                       int64_t rows, int64_t K, int outer_mode, float *out)
+{
+    if (K % 16 || (outer_mode == OUTER_BLOCK128 && K % 128)) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k) {
+            uint8_t byte = codes[r * (K / 2) + k / 2];
+            uint8_t nib = (k & 1) ? (byte >> 4) : (byte & 0xF);
+            float S_b = oracle_e4m3_value(scales[r * (K / 16) + k / 16]);
+            float S_g = outer_mode == OUTER_TENSOR ? gscale[0] : gscale[r * (K / 128) + k / 128];
+            volatile float pv = code_value(nib) * S_b;
+            volatile float dq = pv * S_g;
+            out[r * K + k] = dq;
+        }
+    return 0;
+}
+
+/* exact dequantized value P*S_b*S_g in binary64 (at most 30 significant bits), layout [rows][K] */
+int oracle_dequant_f64(const uint8_t *codes, const uint8_t *scales, const float *gscale,
+                       int64_t rows, int64_t K, int outer_mode, double *out)
+{
+    if (K % 16 || (outer_mode == OUTER_BLOCK128 && K % 128)) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k) {
+            uint8_t byte = codes[r * (K / 2) + k / 2];
+            uint8_t nib = (k & 1) ? (byte >> 4) : (byte & 0xF);
+            double S_b = (double)oracle_e4m3_value(scales[r * (K / 16) + k / 16]);
+            double S_g = (double)(outer_mode == OUTER_TENSOR ? gscale[0] : gscale[r * (K / 128) + k / 128]);
+            out[r * K + k] = (double)code_value(nib) * S_b * S_g;
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ GEMM -- */
+
+/* Sec. 2.3: C[m][n] = sum_k A[m][k] * B[n][k], binary64, k in ascending order.
+ * abs_sum (optional) receives sum_k |A[m][k]| |B[n][k]| for tolerance scaling. */
+int oracle_gemm_nt_f64(const double *A, const double *B, int64_t M, int64_t N, int64_t K,
+                       double *C, double *abs_sum)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double p = A[m * K + k] * B[n * K + k];
+                acc += p;
+                aacc += fabs(p);
+            }
+            C[m * N + n] = acc;
+            if (abs_sum) abs_sum[m * N + n] = aacc;
+        }
+    return 0;
+}
+
+/* ---------------------------------------------------------------- helpers -- */
+
+void oracle_bf16_to_f32(const uint16_t *src, int64_t n, float *dst)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t b = (uint32_t)src[i] << 16;
+        memcpy(dst + i, &b, 4);
+    }
+}
+
+/* dst[c][r] = src[r][c] */
+void oracle_transpose_f32(const float *src, int64_t R, int64_t C, float *dst)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < C; ++c)
+        for (int64_t r = 0; r < R; ++r) dst[c * R + r] = src[r * C + c];
+}
+
+float oracle_abs_max_f32(const float *x, int64_t n) { return abs_max(x, n); }
