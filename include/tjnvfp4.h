@@ -1,0 +1,154 @@
+/*
+ * tjnvfp4 - NVFP4 fully-quantized linear layer for AMD MI355X (gfx950), C ABI.
+ *
+ * The operations are those of TetraJet-v2 (arXiv 2510.27527):
+ *   Sec. 2.1  E2M1 elements, groups of 16 sharing one E4M3 scale, deterministic
+ *             (nearest) and stochastic rounding;
+ *   Sec. 2.2  double-block scaling: an FP32 outer scale S_global over an outer
+ *             group (the whole tensor, or 128 consecutive elements) and an E4M3
+ *             inner scale S_block per 16 elements;
+ *   Sec. 2.3  the quantized linear layer
+ *               Y  = Q1_D(X)    x Q2_D(W^T)
+ *               dX = Q3_S(dY)   x Q4_S(W_hat)
+ *               dW = Q5_S(dY^T) x Q6_S(X_hat)
+ *             with X [N x D], W [C x D], Y, dY [N x C]; every operand is grouped
+ *             along the reduction axis of its product.
+ *
+ * Conventions
+ *   - Every data pointer is DEVICE memory owned by the caller, 16-byte aligned.
+ *     The library allocates nothing, frees nothing and never synchronises: each
+ *     call validates its arguments on the host, then enqueues kernels on
+ *     `stream` (a hipStream_t passed as void*, NULL = default stream) and returns.
+ *   - Descriptor structs (nvfp4_tensor, nvfp4_qcfg) are HOST memory, read during
+ *     the call only.
+ *   - Return value: 0 on success, a negative NVFP4_ERR_* otherwise; on error
+ *     nothing has been enqueued unless the code is NVFP4_ERR_HIP.
+ *   - `ws` is a scratch buffer of at least nvfp4_workspace_bytes(...) bytes that
+ *     must stay untouched until the enqueued work has finished.  Two calls that
+ *     overlap in time need different workspaces.
+ *
+ * Storage of a quantized operand (K = grouped, contiguous axis, K % 16 == 0):
+ *   codes  [rows][K/2]   two E2M1 codes per byte, element 2j in the low nibble;
+ *                        code = sign<<3 | index into {0,.5,1,1.5,2,3,4,6}
+ *   scales [rows][K/16]  E4M3 (bias 7, no infinity, max 448 = 0x7E), row-major
+ *   gscale               FP32 outer scale(s): [1] (NVFP4_OUTER_TENSOR) or
+ *                        [rows][K/128] (NVFP4_OUTER_BLOCK128)
+ *   value(r,k) = E2M1(code) * E4M3(scales[r][k/16]) * gscale[...]
+ */
+#ifndef TJNVFP4_H
+#define TJNVFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    NVFP4_OK = 0,
+    NVFP4_ERR_NULL = -1,      /* a required pointer is NULL */
+    NVFP4_ERR_SHAPE = -2,     /* negative size, K % 16 != 0, K % 128 != 0 in BLOCK128 mode, > 2^33 elements */
+    NVFP4_ERR_ENUM = -3,      /* unknown enum value, or a combination this build does not provide */
+    NVFP4_ERR_WORKSPACE = -4, /* ws is NULL or smaller than nvfp4_workspace_bytes() */
+    NVFP4_ERR_ALIGN = -5,     /* a device pointer is not 16-byte aligned */
+    NVFP4_ERR_MISMATCH = -6,  /* operand descriptors disagree with each other or with N, D, C */
+    NVFP4_ERR_HIP = -7        /* a HIP launch failed; see hipGetLastError() */
+};
+
+enum { NVFP4_ROUND_RTN = 0, NVFP4_ROUND_SR = 1 };                 /* Sec. 2.1: deterministic / stochastic   */
+enum { NVFP4_SCALE_DEFAULT = 0, NVFP4_SCALE_NE = 1, NVFP4_SCALE_UP = 2 }; /* E4M3 rounding of S_block; DEFAULT = NE for RTN, UP for SR */
+enum { NVFP4_OUTER_TENSOR = 0, NVFP4_OUTER_BLOCK128 = 1 };       /* Sec. 2.2 outer group: tensor / 1x128   */
+enum { NVFP4_SRC_BF16 = 0, NVFP4_SRC_NVFP4 = 1 };                 /* source kind of nvfp4_quantize         */
+enum { NVFP4_OUT_BF16 = 0, NVFP4_OUT_F32 = 1 };                   /* output element type of the products   */
+enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_GEMM = 1, NVFP4_OP_LINEAR_FWD = 2,
+       NVFP4_OP_LINEAR_BWD_DX = 3, NVFP4_OP_LINEAR_BWD_DW = 4 };
+
+/* One quantized operand.  The caller fills the four pointers with buffers of the
+ * sizes given above; the producing call fills rows, K and outer_mode. */
+typedef struct nvfp4_tensor {
+    uint8_t *codes;      /* device */
+    uint8_t *scales;     /* device */
+    float   *gscale;     /* device */
+    float   *amax_deq;   /* device [1], optional (may be NULL): receives max |value| over the tensor, rounded to
+                            FP32; needed when the operand is later re-quantized in TENSOR mode (Q4, Q6) */
+    int64_t  rows, K;
+    int32_t  outer_mode;
+    int32_t  reserved;
+} nvfp4_tensor;
+
+/* Parameters of one quantization. */
+typedef struct nvfp4_qcfg {
+    int32_t  rounding;     /* NVFP4_ROUND_*  */
+    int32_t  scale_round;  /* NVFP4_SCALE_*  */
+    int32_t  outer_mode;   /* NVFP4_OUTER_*  */
+    uint32_t tensor_id;    /* stochastic rounding: stream id; the random bits of output element e (index in the
+                              output's own [rows x K] view) depend only on (seed, tensor_id, e) */
+    uint64_t seed;
+    const float *amax_in;  /* device [1], optional, TENSOR mode: max |src| if the caller already has it */
+} nvfp4_qcfg;
+
+/*
+ * Quantize (Sec. 2.1-2.2).  src is a bf16 [R x C] row-major device array (NVFP4_SRC_BF16) or a HOST pointer to an
+ * nvfp4_tensor describing an [R x C] operand (NVFP4_SRC_NVFP4, re-quantization of Sec. 2.3's X_hat / W_hat, which
+ * starts from the FP32 value code*scale*gscale).  axis 0: groups run along C, out describes [R x C] (K = C).
+ * axis 1: groups run along R (16 x 1 groups), out describes the transpose [C x R] (K = R).
+ * In TENSOR mode the tensor maximum is taken from cfg->amax_in, else from src->amax_deq (NVFP4 source), else by a
+ * reduction pass over src.  Errors: NULL, SHAPE, ENUM, WORKSPACE, ALIGN, MISMATCH.
+ */
+int nvfp4_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis,
+                   const nvfp4_qcfg *cfg, nvfp4_tensor *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Out[M x N] = A[M x K] * B[N x K]^T on two quantized operands grouped along K (Sec. 2.3: all three products take
+ * this form).  Products of dequantized 16-bit values are exact; accumulation is FP32; the outer scales multiply
+ * the accumulator at the end; Out is row-major bf16 or f32.  Both operands must be in TENSOR outer mode.
+ */
+int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Forward (Sec. 2.3, first line): quantizes X [N x D] and W [C x D] (bf16, round-to-nearest, groups along D) into
+ * Xq_ctx / Wq_ctx, which the caller keeps for the backward calls, and writes Y [N x C].
+ */
+int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t C,
+                     void *Y, int out_dtype, nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx,
+                     int outer_mode, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Input gradient (Sec. 2.3, second line): dX [N x D] = Q3_S(dY) x Q4_S(W_hat); dY [N x C] bf16, W_hat = Wq_ctx of
+ * the forward call, both re-grouped along C with stochastic rounding.  Streams: tensor ids layer_id*8+3 and +4.
+ */
+int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D, int64_t C,
+                        void *dX, int out_dtype, uint64_t seed, uint32_t layer_id,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Weight gradient (Sec. 2.3, third line): dW [C x D] = Q5_S(dY^T) x Q6_S(X_hat); both operands re-grouped along N
+ * with stochastic rounding.  Streams: tensor ids layer_id*8+5 and +6.
+ */
+int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C,
+                        void *dW, int out_dtype, uint64_t seed, uint32_t layer_id,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Scratch bytes an operation needs.  op = NVFP4_OP_*.  QUANTIZE: (N, D) = (R, C) of the source, C ignored.
+ * GEMM: Out is [N x C] with reduction length D.  LINEAR_*: as in the calls above.  Returns 0 for a bad op.
+ */
+size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_mode);
+
+/* Tensor maximum of |x| of a bf16 device array of n elements (n % 8 == 0) into amax_out (device [1]). */
+int nvfp4_amax_bf16(const void *src, int64_t n, float *amax_out, void *ws, size_t ws_bytes, void *stream);
+
+/* The 64-bit stream key the stochastic-rounding generator derives from (seed, tensor_id); host-only helper. */
+uint64_t nvfp4_stream_key(uint64_t seed, uint32_t tensor_id);
+
+const char *nvfp4_strerror(int code);
+
+/* "tjnvfp4 <version> gfx950" */
+const char *nvfp4_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TJNVFP4_H */

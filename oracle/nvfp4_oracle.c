@@ -19,8 +19,10 @@
  *   R1  All quantizer arithmetic that decides a code is IEEE binary32,
  *       round-to-nearest-even, one rounding per written operation, no fused
  *       multiply-add, subnormals kept.  Order:  S_g = amax_g / 2688 ;
- *       c_g = 6 * S_g ; s = amax_b / c_g ; S_b = e4m3(s) ; d = S_g * S_b ;
- *       r = 1 / d ; y = x * r ; a = min(|y|, 6).
+ *       i_g = 1 / S_g ; s = amax_b * (i_g * (1/6)) ; S_b = e4m3(s) ;
+ *       r = i_g * (1 / S_b) ; y = x * r ; a = min(|y|, 6), with 1/6 the binary32
+ *       constant.  (Divisions are per outer group or per scale value, never
+ *       per element.)
  *   R2  S_g is floored at 2^-100 (keeps 1/d finite); an all-zero outer group
  *       gets S_g = 1 and all-zero scales and codes.
  *   R3  The block scale is rounded to E4M3 (bias 7, no infinity, max 448,
@@ -37,8 +39,9 @@
  *   R6  The random 16 bits of output element e (index in the quantized
  *       operand's own [rows x K] view) come from a counter-based hash of the
  *       pair index e>>1, keyed by (seed, tensor id); see rand16() below.
- *   R7  A code is sign<<3 | index into the ascending value set; -0 is never
- *       emitted.  Element k of a row sits in byte k/2, even k in the low nibble.
+ *   R7  A code is sign<<3 | index into the ascending value set, the sign bit
+ *       being the input's sign bit (so -0 codes occur and decode to -0).
+ *       Element k of a row sits in byte k/2, even k in the low nibble.
  *   R8  Re-quantizing an NVFP4 tensor (Q4, Q6 of Sec. 2.3) starts from its
  *       binary32 dequantized value  x = RN( (P * S_b) * S_g ).
  *
@@ -217,16 +220,18 @@ int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
                 S_g = oracle_global_scale(abs_max(xr + g * 128, 128));
                 gscale[r * outer_per_row + g] = S_g;
             }
-            volatile float c_g = 6.0f * S_g;
+            volatile float inv_sg = 1.0f / S_g;
+            volatile float sixth = 1.0f / 6.0f;
+            volatile float inv_cg = inv_sg * sixth;                     /* 1 / (6 S_global) */
             for (int64_t b = g * outer_len / 16; b < (g + 1) * outer_len / 16; ++b) {
                 const float *xb = xr + b * 16;
                 float amax_b = abs_max(xb, 16);
-                volatile float s = amax_b / c_g;                       /* Sec. 2.2, S_block */
+                volatile float s = amax_b * inv_cg;                    /* Sec. 2.2, S_block */
                 uint8_t sc = oracle_e4m3_round(s, scale_round);
                 scales[r * (K / 16) + b] = sc;
                 float S_b = oracle_e4m3_value(sc);
-                volatile float d = S_g * S_b;
-                volatile float rcp = sc == 0 ? 0.0f : 1.0f / d;
+                volatile float inv_sb = sc == 0 ? 0.0f : 1.0f / S_b;
+                volatile float rcp = inv_sg * inv_sb;                   /* 1 / (S_global * S_block) */
                 for (int i = 0; i < 16; ++i) {
                     int64_t k = b * 16 + i;
                     volatile float y = xb[i] * rcp;                    /* Sec. 2.2, argument of round_FP4 */
@@ -234,7 +239,7 @@ int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
                     int m;
                     if (rounding == ROUND_RTN) m = oracle_round_rtn(a);
                     else m = oracle_round_sr(a, oracle_rand16((uint64_t)(r * K + k), key));
-                    int neg = signbit(xb[i]) && m != 0;
+                    int neg = signbit(xb[i]) != 0;
                     uint8_t nib = (uint8_t)((neg << 3) | m);
                     uint8_t *byte = codes + r * (K / 2) + k / 2;
                     if (k & 1) *byte = (uint8_t)((*byte & 0x0F) | (nib << 4));

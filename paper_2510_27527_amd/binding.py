@@ -1,0 +1,228 @@
+"""ctypes binding of libtjnvfp4.so: argument marshalling only.
+
+Every step of the path (maxima, quantizers, re-quantizers, matrix products) runs in the
+library's HIP kernels; this module turns torch CUDA tensors into raw device pointers and
+the current torch stream into a hipStream_t.  There is no CPU fallback: if the library is
+missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtjnvfp4.so")
+
+ROUND_RTN, ROUND_SR = 0, 1
+SCALE_DEFAULT, SCALE_NE, SCALE_UP = 0, 1, 2
+OUTER_TENSOR, OUTER_BLOCK128 = 0, 1
+SRC_BF16, SRC_NVFP4 = 0, 1
+OUT_BF16, OUT_F32 = 0, 1
+OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW = 0, 1, 2, 3, 4
+
+EXPORTS = ["nvfp4_quantize", "nvfp4_gemm_nt", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw",
+           "nvfp4_workspace_bytes", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
+
+
+class NVFP4Error(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, lib().nvfp4_strerror(code).decode(), code))
+
+
+class CTensor(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("scales", C.c_void_p), ("gscale", C.c_void_p), ("amax_deq", C.c_void_p),
+                ("rows", C.c_int64), ("K", C.c_int64), ("outer_mode", C.c_int32), ("reserved", C.c_int32)]
+
+
+class CQcfg(C.Structure):
+    _fields_ = [("rounding", C.c_int32), ("scale_round", C.c_int32), ("outer_mode", C.c_int32),
+                ("tensor_id", C.c_uint32), ("seed", C.c_uint64), ("amax_in", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the library (raises OSError if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError("libtjnvfp4.so is not built: run `python -m paper_2510_27527_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, u64, u32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_uint32, C.c_size_t
+        L.nvfp4_quantize.restype = i32
+        L.nvfp4_quantize.argtypes = [vp, i32, i64, i64, i32, C.POINTER(CQcfg), C.POINTER(CTensor), vp, sz, vp]
+        L.nvfp4_gemm_nt.restype = i32
+        L.nvfp4_gemm_nt.argtypes = [C.POINTER(CTensor), C.POINTER(CTensor), vp, i32, vp, sz, vp]
+        L.nvfp4_linear_fwd.restype = i32
+        L.nvfp4_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, i32, C.POINTER(CTensor), C.POINTER(CTensor),
+                                       i32, vp, sz, vp]
+        L.nvfp4_linear_bwd_dx.restype = i32
+        L.nvfp4_linear_bwd_dx.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, vp, sz, vp]
+        L.nvfp4_linear_bwd_dw.restype = i32
+        L.nvfp4_linear_bwd_dw.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, vp, sz, vp]
+        L.nvfp4_workspace_bytes.restype = sz
+        L.nvfp4_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
+        L.nvfp4_amax_bf16.restype = i32
+        L.nvfp4_amax_bf16.argtypes = [vp, i64, vp, vp, sz, vp]
+        L.nvfp4_stream_key.restype = u64
+        L.nvfp4_stream_key.argtypes = [u64, u32]
+        L.nvfp4_strerror.restype = C.c_char_p
+        L.nvfp4_strerror.argtypes = [i32]
+        L.nvfp4_version.restype = C.c_char_p
+        L.nvfp4_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise NVFP4Error(rc, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+@dataclass
+class NVFP4Tensor:
+    """Device buffers of one quantized operand [rows, K] (K contiguous, grouped axis)."""
+    codes: torch.Tensor      # uint8 [rows, K/2]
+    scales: torch.Tensor     # uint8 [rows, K/16]
+    gscale: torch.Tensor     # float32 [1] or [rows, K/128]
+    amax_deq: Optional[torch.Tensor]   # float32 [1] or None
+    rows: int
+    K: int
+    outer: int
+
+    def c_struct(self) -> CTensor:
+        return CTensor(_ptr(self.codes), _ptr(self.scales), _ptr(self.gscale), _ptr(self.amax_deq),
+                       self.rows, self.K, self.outer, 0)
+
+
+def alloc_nvfp4(rows: int, K: int, outer: int = OUTER_TENSOR, device="cuda", with_amax: bool = True) -> NVFP4Tensor:
+    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=device)
+    scales = torch.empty((rows, K // 16), dtype=torch.uint8, device=device)
+    gshape = (1,) if outer == OUTER_TENSOR else (rows, max(K // 128, 1))
+    gscale = torch.empty(gshape, dtype=torch.float32, device=device)
+    amax = torch.zeros((1,), dtype=torch.float32, device=device) if with_amax else None
+    return NVFP4Tensor(codes, scales, gscale, amax, rows, K, outer)
+
+
+def workspace_bytes(op: int, N: int, D: int, Cc: int, outer: int = OUTER_TENSOR) -> int:
+    return int(lib().nvfp4_workspace_bytes(op, N, D, Cc, outer))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty((max(int(nbytes), 16),), dtype=torch.uint8, device=device)
+
+
+def stream_key(seed: int, tensor_id: int) -> int:
+    return int(lib().nvfp4_stream_key(seed, tensor_id))
+
+
+def amax_bf16(src: torch.Tensor, ws: torch.Tensor) -> torch.Tensor:
+    out = torch.empty((1,), dtype=torch.float32, device=src.device)
+    _check(lib().nvfp4_amax_bf16(_ptr(src), src.numel(), _ptr(out), _ptr(ws), ws.numel(), _stream()), "nvfp4_amax_bf16")
+    return out
+
+
+def quantize(src, axis: int, rounding: int, out: Optional[NVFP4Tensor] = None, *, scale_round: int = SCALE_DEFAULT,
+             outer: int = OUTER_TENSOR, seed: int = 0, tensor_id: int = 0, amax_in: Optional[torch.Tensor] = None,
+             ws: Optional[torch.Tensor] = None) -> NVFP4Tensor:
+    """nvfp4_quantize: src is a bf16 [R, C] tensor or an NVFP4Tensor."""
+    if isinstance(src, NVFP4Tensor):
+        kind, R, Cc = SRC_NVFP4, src.rows, src.K
+        cs = src.c_struct()
+        src_arg = C.cast(C.pointer(cs), C.c_void_p)
+        dev = src.codes.device
+    else:
+        assert src.dtype == torch.bfloat16 and src.dim() == 2 and src.is_contiguous()
+        kind, (R, Cc) = SRC_BF16, src.shape
+        src_arg = _ptr(src)
+        dev = src.device
+    rows, K = (R, Cc) if axis == 0 else (Cc, R)
+    if out is None:
+        out = alloc_nvfp4(rows, K, outer, dev)
+    if ws is None:
+        ws = alloc_workspace(workspace_bytes(OP_QUANTIZE, R, Cc, 0, outer), dev)
+    cfg = CQcfg(rounding, scale_round, outer, tensor_id, seed, _ptr(amax_in))
+    co = out.c_struct()
+    rc = lib().nvfp4_quantize(src_arg, kind, R, Cc, axis, C.byref(cfg), C.byref(co), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "nvfp4_quantize")
+    out.rows, out.K, out.outer = co.rows, co.K, co.outer_mode
+    return out
+
+
+def _out_tensor(M, N, out_dtype, device):
+    return torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32, device=device)
+
+
+def gemm_nt(A: NVFP4Tensor, B: NVFP4Tensor, out_dtype: int = OUT_BF16, out: Optional[torch.Tensor] = None,
+            ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    dev = A.codes.device
+    if out is None:
+        out = _out_tensor(A.rows, B.rows, out_dtype, dev)
+    if ws is None:
+        ws = alloc_workspace(workspace_bytes(OP_GEMM, A.rows, A.K, B.rows), dev)
+    ca, cb = A.c_struct(), B.c_struct()
+    rc = lib().nvfp4_gemm_nt(C.byref(ca), C.byref(cb), _ptr(out), out_dtype, _ptr(ws), ws.numel(), _stream())
+    _check(rc, "nvfp4_gemm_nt")
+    return out
+
+
+def linear_fwd(X: torch.Tensor, W: torch.Tensor, out_dtype: int = OUT_BF16, *, Y: Optional[torch.Tensor] = None,
+               Xq: Optional[NVFP4Tensor] = None, Wq: Optional[NVFP4Tensor] = None,
+               ws: Optional[torch.Tensor] = None, outer: int = OUTER_TENSOR):
+    N, D = X.shape
+    Cc, D2 = W.shape
+    assert D == D2
+    dev = X.device
+    Y = _out_tensor(N, Cc, out_dtype, dev) if Y is None else Y
+    Xq = alloc_nvfp4(N, D, outer, dev) if Xq is None else Xq
+    Wq = alloc_nvfp4(Cc, D, outer, dev) if Wq is None else Wq
+    ws = alloc_workspace(workspace_bytes(OP_LINEAR_FWD, N, D, Cc, outer), dev) if ws is None else ws
+    cx, cw = Xq.c_struct(), Wq.c_struct()
+    rc = lib().nvfp4_linear_fwd(_ptr(X), _ptr(W), N, D, Cc, _ptr(Y), out_dtype, C.byref(cx), C.byref(cw), outer,
+                                _ptr(ws), ws.numel(), _stream())
+    _check(rc, "nvfp4_linear_fwd")
+    Xq.rows, Xq.K, Xq.outer = cx.rows, cx.K, cx.outer_mode
+    Wq.rows, Wq.K, Wq.outer = cw.rows, cw.K, cw.outer_mode
+    return Y, Xq, Wq
+
+
+def linear_bwd_dx(dY: torch.Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
+                  dX: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    N, Cc = dY.shape
+    D = Wq.K
+    dev = dY.device
+    dX = _out_tensor(N, D, out_dtype, dev) if dX is None else dX
+    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DX, N, D, Cc), dev) if ws is None else ws
+    cw = Wq.c_struct()
+    rc = lib().nvfp4_linear_bwd_dx(_ptr(dY), C.byref(cw), N, D, Cc, _ptr(dX), out_dtype, seed, layer_id,
+                                   _ptr(ws), ws.numel(), _stream())
+    _check(rc, "nvfp4_linear_bwd_dx")
+    return dX
+
+
+def linear_bwd_dw(dY: torch.Tensor, Xq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
+                  dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    N, Cc = dY.shape
+    D = Xq.K
+    dev = dY.device
+    dW = _out_tensor(Cc, D, out_dtype, dev) if dW is None else dW
+    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DW, N, D, Cc), dev) if ws is None else ws
+    cx = Xq.c_struct()
+    rc = lib().nvfp4_linear_bwd_dw(_ptr(dY), C.byref(cx), N, D, Cc, _ptr(dW), out_dtype, seed, layer_id,
+                                   _ptr(ws), ws.numel(), _stream())
+    _check(rc, "nvfp4_linear_bwd_dw")
+    return dW

@@ -1,0 +1,398 @@
+// C-ABI layer of tjnvfp4: host-side argument validation, workspace carving and the composition
+// of the kernels into the four calls of the NVFP4 linear layer (TetraJet-v2 Sec. 2.3).
+// Validation happens before the first HIP call, so every error path can be exercised on a
+// machine without a GPU.
+#include "../../include/tjnvfp4.h"
+#include "internal.h"
+
+namespace tj {
+
+// (seed, tensor id) -> 64-bit stream key; low word k0, high word k1
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+uint64_t stream_key(uint64_t seed, uint32_t tensor_id)
+{
+    const uint64_t a = mix64(seed + 0x9E3779B97F4A7C15ull);
+    const uint64_t b = ((uint64_t)tensor_id + 1ull) * 0xD1B54A32D192ED03ull;
+    return mix64(a ^ b);
+}
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int64_t kMaxElems = (int64_t)1 << 33;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// sequential carving of the caller's workspace
+struct Carver {
+    uint8_t *base;
+    size_t size, used;
+    void *take(size_t bytes)
+    {
+        const size_t off = used;
+        used += align_up(bytes);
+        return (base && used <= size) ? base + off : nullptr;
+    }
+};
+
+size_t partials_bytes() { return align_up(sizeof(float) * kMaxAmaxPartials); }
+size_t packed_bytes(int64_t rows, int64_t K)
+{
+    return align_up((size_t)(rows * K / 2)) + align_up((size_t)(rows * K / 16)) + align_up(sizeof(float));
+}
+
+int check_shape(int64_t rows, int64_t K, int outer)
+{
+    if (rows < 0 || K < 0) return NVFP4_ERR_SHAPE;
+    if (K % 16 != 0) return NVFP4_ERR_SHAPE;
+    if (outer == NVFP4_OUTER_BLOCK128 && K % 128 != 0) return NVFP4_ERR_SHAPE;
+    if (rows > 0 && K > kMaxElems / rows) return NVFP4_ERR_SHAPE;
+    return NVFP4_OK;
+}
+
+int check_tensor_ptrs(const nvfp4_tensor *t)
+{
+    if (!t || !t->codes || !t->scales || !t->gscale) return NVFP4_ERR_NULL;
+    if (!aligned16(t->codes) || !aligned16(t->scales) || (reinterpret_cast<uintptr_t>(t->gscale) & 3u))
+        return NVFP4_ERR_ALIGN;
+    if (t->amax_deq && (reinterpret_cast<uintptr_t>(t->amax_deq) & 3u)) return NVFP4_ERR_ALIGN;
+    return NVFP4_OK;
+}
+
+// a gemm operand must be a finished TENSOR-mode operand with K % 64 == 0
+int check_gemm_operand(const nvfp4_tensor *t)
+{
+    int rc = check_tensor_ptrs(t);
+    if (rc) return rc;
+    if (t->outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;
+    rc = check_shape(t->rows, t->K, t->outer_mode);
+    if (rc) return rc;
+    if (t->K % 64 != 0) return NVFP4_ERR_SHAPE;
+    return NVFP4_OK;
+}
+
+struct QuantPlan {
+    int src_kind, axis;
+    int64_t R, C;
+    int64_t out_rows, out_K;
+    int rounding, scale_up, outer;
+    bool need_partials;
+};
+
+int plan_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis, const nvfp4_qcfg *cfg,
+                  const nvfp4_tensor *out, QuantPlan *pl)
+{
+    if (!src || !cfg || !out) return NVFP4_ERR_NULL;
+    if (src_kind != NVFP4_SRC_BF16 && src_kind != NVFP4_SRC_NVFP4) return NVFP4_ERR_ENUM;
+    if (axis != 0 && axis != 1) return NVFP4_ERR_ENUM;
+    if (cfg->rounding != NVFP4_ROUND_RTN && cfg->rounding != NVFP4_ROUND_SR) return NVFP4_ERR_ENUM;
+    if (cfg->scale_round < NVFP4_SCALE_DEFAULT || cfg->scale_round > NVFP4_SCALE_UP) return NVFP4_ERR_ENUM;
+    if (cfg->outer_mode != NVFP4_OUTER_TENSOR && cfg->outer_mode != NVFP4_OUTER_BLOCK128) return NVFP4_ERR_ENUM;
+    if (R < 0 || C < 0) return NVFP4_ERR_SHAPE;
+    pl->src_kind = src_kind;
+    pl->axis = axis;
+    pl->R = R;
+    pl->C = C;
+    pl->out_rows = axis == 0 ? R : C;
+    pl->out_K = axis == 0 ? C : R;
+    pl->rounding = cfg->rounding;
+    pl->scale_up = cfg->scale_round == NVFP4_SCALE_DEFAULT ? (cfg->rounding == NVFP4_ROUND_SR)
+                                                           : (cfg->scale_round == NVFP4_SCALE_UP);
+    pl->outer = cfg->outer_mode;
+    int rc = check_shape(pl->out_rows, pl->out_K, pl->outer);
+    if (rc) return rc;
+    rc = check_tensor_ptrs(out);
+    if (rc) return rc;
+    if (cfg->amax_in && (reinterpret_cast<uintptr_t>(cfg->amax_in) & 3u)) return NVFP4_ERR_ALIGN;
+    if (src_kind == NVFP4_SRC_BF16) {
+        if (!aligned16(src)) return NVFP4_ERR_ALIGN;
+        if (axis == 1 && C % 8 != 0) return NVFP4_ERR_SHAPE;           // 128-bit loads along C
+        if (axis == 1 && pl->outer == NVFP4_OUTER_BLOCK128) return NVFP4_ERR_ENUM;
+        pl->need_partials = pl->outer == NVFP4_OUTER_TENSOR && cfg->amax_in == nullptr;
+    } else {
+        const nvfp4_tensor *s = static_cast<const nvfp4_tensor *>(src);
+        rc = check_tensor_ptrs(s);
+        if (rc) return rc;
+        if (s->rows != R || s->K != C) return NVFP4_ERR_MISMATCH;
+        rc = check_shape(R, C, s->outer_mode);
+        if (rc) return rc;
+        // provided: TENSOR-mode source re-grouped along the other axis in TENSOR mode (Q4, Q6)
+        if (axis != 1 || s->outer_mode != NVFP4_OUTER_TENSOR || pl->outer != NVFP4_OUTER_TENSOR)
+            return NVFP4_ERR_ENUM;
+        if (!cfg->amax_in && !s->amax_deq) return NVFP4_ERR_NULL;
+        pl->need_partials = false;
+    }
+    return NVFP4_OK;
+}
+
+int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nvfp4_tensor *out, float *partials,
+                 hipStream_t st)
+{
+    QuantParams p{};
+    p.rounding = pl.rounding;
+    p.scale_up = pl.scale_up ? 1 : 0;
+    p.outer = pl.outer;
+    const uint64_t key = stream_key(cfg->seed, cfg->tensor_id);
+    p.k0 = (uint32_t)key;
+    p.k1 = (uint32_t)(key >> 32);
+    QuantOut o{out->codes, out->scales, out->gscale, out->amax_deq};
+    out->rows = pl.out_rows;
+    out->K = pl.out_K;
+    out->outer_mode = pl.outer;
+    if (pl.out_rows == 0 || pl.out_K == 0) return NVFP4_OK;
+    hipError_t e;
+    if (pl.src_kind == NVFP4_SRC_BF16) {
+        if (pl.outer == NVFP4_OUTER_TENSOR) {
+            if (cfg->amax_in) {
+                p.amax_scalar = cfg->amax_in;
+            } else {
+                p.npart = launch_amax_partials(src, pl.R * pl.C, partials, st);
+                p.amax_partials = partials;
+            }
+        }
+        if (o.amax_deq && pl.rounding == NVFP4_ROUND_RTN) launch_zero_scalar(o.amax_deq, st);
+        if (pl.rounding != NVFP4_ROUND_RTN) o.amax_deq = nullptr;
+        e = pl.axis == 0 ? launch_quant_row_bf16(src, pl.R, pl.C, p, o, st)
+                         : launch_quant_col_bf16(src, pl.R, pl.C, p, o, st);
+    } else {
+        const nvfp4_tensor *s = static_cast<const nvfp4_tensor *>(src);
+        p.amax_scalar = cfg->amax_in ? cfg->amax_in : s->amax_deq;
+        o.amax_deq = nullptr;
+        PackedSrc ps{s->codes, s->scales, s->gscale, s->outer_mode};
+        e = launch_requant_col(ps, pl.R, pl.C, p, o, st);
+    }
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int run_gemm(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *ws, size_t ws_bytes,
+             hipStream_t st)
+{
+    GemmOperand a{A->codes, A->scales, A->gscale, A->rows};
+    GemmOperand b{B->codes, B->scales, B->gscale, B->rows};
+    const hipError_t e = launch_gemm_nt(a, b, A->K, Out, out_dtype == NVFP4_OUT_F32, ws, ws_bytes, st);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int check_out(const void *p, int out_dtype)
+{
+    if (!p) return NVFP4_ERR_NULL;
+    if (out_dtype != NVFP4_OUT_BF16 && out_dtype != NVFP4_OUT_F32) return NVFP4_ERR_ENUM;
+    if (!aligned16(p)) return NVFP4_ERR_ALIGN;
+    return NVFP4_OK;
+}
+
+// carve a temporary operand [rows x K] out of the workspace
+bool carve_tensor(Carver &cv, int64_t rows, int64_t K, nvfp4_tensor *t)
+{
+    t->codes = static_cast<uint8_t *>(cv.take((size_t)(rows * K / 2)));
+    t->scales = static_cast<uint8_t *>(cv.take((size_t)(rows * K / 16)));
+    t->gscale = static_cast<float *>(cv.take(sizeof(float)));
+    t->amax_deq = nullptr;
+    t->rows = rows;
+    t->K = K;
+    t->outer_mode = NVFP4_OUTER_TENSOR;
+    t->reserved = 0;
+    return t->codes && t->scales && t->gscale;
+}
+
+}  // namespace
+}  // namespace tj
+
+using namespace tj;
+
+extern "C" {
+
+const char *nvfp4_strerror(int code)
+{
+    switch (code) {
+        case NVFP4_OK: return "ok";
+        case NVFP4_ERR_NULL: return "a required pointer is NULL";
+        case NVFP4_ERR_SHAPE: return "bad shape (negative, grouped axis not a multiple of 16/64/128, or too large)";
+        case NVFP4_ERR_ENUM: return "unknown enum value or unsupported combination";
+        case NVFP4_ERR_WORKSPACE: return "workspace missing or too small";
+        case NVFP4_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case NVFP4_ERR_MISMATCH: return "operand descriptors disagree";
+        case NVFP4_ERR_HIP: return "HIP launch failed";
+        default: return "unknown error code";
+    }
+}
+
+const char *nvfp4_version(void) { return "tjnvfp4 0.1 gfx950"; }
+
+uint64_t nvfp4_stream_key(uint64_t seed, uint32_t tensor_id) { return stream_key(seed, tensor_id); }
+
+size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_mode)
+{
+    (void)outer_mode;
+    if (N < 0 || D < 0 || C < 0) return 0;
+    switch (op) {
+        case NVFP4_OP_QUANTIZE: return partials_bytes();
+        case NVFP4_OP_GEMM: return align_up(gemm_workspace_bytes(N, C, D));
+        case NVFP4_OP_LINEAR_FWD: return 2 * partials_bytes() + align_up(gemm_workspace_bytes(N, C, D));
+        case NVFP4_OP_LINEAR_BWD_DX:
+            return partials_bytes() + packed_bytes(N, C) + packed_bytes(D, C) + align_up(gemm_workspace_bytes(N, D, C));
+        case NVFP4_OP_LINEAR_BWD_DW:
+            return partials_bytes() + packed_bytes(C, N) + packed_bytes(D, N) + align_up(gemm_workspace_bytes(C, D, N));
+        default: return 0;
+    }
+}
+
+int nvfp4_amax_bf16(const void *src, int64_t n, float *amax_out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!src || !amax_out) return NVFP4_ERR_NULL;
+    if (n < 0 || n % 8 != 0) return NVFP4_ERR_SHAPE;
+    if (!aligned16(src)) return NVFP4_ERR_ALIGN;
+    if (!ws || ws_bytes < partials_bytes()) return NVFP4_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int npart = launch_amax_partials(src, n, static_cast<float *>(ws), st);
+    launch_amax_final(static_cast<float *>(ws), npart, amax_out, st);
+    return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis, const nvfp4_qcfg *cfg,
+                   nvfp4_tensor *out, void *ws, size_t ws_bytes, void *stream)
+{
+    QuantPlan pl{};
+    const int rc = plan_quantize(src, src_kind, R, C, axis, cfg, out, &pl);
+    if (rc) return rc;
+    if (pl.need_partials && (!ws || ws_bytes < partials_bytes())) return NVFP4_ERR_WORKSPACE;
+    if (ws && !aligned16(ws)) return NVFP4_ERR_ALIGN;
+    return run_quantize(src, pl, cfg, out, static_cast<float *>(ws), static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *ws, size_t ws_bytes,
+                  void *stream)
+{
+    int rc = check_gemm_operand(A);
+    if (rc) return rc;
+    rc = check_gemm_operand(B);
+    if (rc) return rc;
+    rc = check_out(Out, out_dtype);
+    if (rc) return rc;
+    if (A->K != B->K) return NVFP4_ERR_MISMATCH;
+    if (ws && !aligned16(ws)) return NVFP4_ERR_ALIGN;
+    if (gemm_workspace_bytes(A->rows, B->rows, A->K) > 0 && (!ws || ws_bytes < gemm_workspace_bytes(A->rows, B->rows, A->K)))
+        return NVFP4_ERR_WORKSPACE;
+    return run_gemm(A, B, Out, out_dtype, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t C, void *Y, int out_dtype,
+                     nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx, int outer_mode, void *ws, size_t ws_bytes,
+                     void *stream)
+{
+    if (!X || !W) return NVFP4_ERR_NULL;
+    if (outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;      // the products take tensor-mode operands
+    if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
+    if (D % 64 != 0) return NVFP4_ERR_SHAPE;
+    int rc = check_out(Y, out_dtype);
+    if (rc) return rc;
+    nvfp4_qcfg cfg{};
+    cfg.rounding = NVFP4_ROUND_RTN;
+    cfg.scale_round = NVFP4_SCALE_DEFAULT;
+    cfg.outer_mode = outer_mode;
+    QuantPlan px{}, pw{};
+    rc = plan_quantize(X, NVFP4_SRC_BF16, N, D, 0, &cfg, Xq_ctx, &px);
+    if (rc) return rc;
+    rc = plan_quantize(W, NVFP4_SRC_BF16, C, D, 0, &cfg, Wq_ctx, &pw);
+    if (rc) return rc;
+    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_FWD, N, D, C, outer_mode)) return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
+    float *part_x = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
+    float *part_w = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
+    const size_t gbytes = gemm_workspace_bytes(N, C, D);
+    void *gws = gbytes ? cv.take(gbytes) : nullptr;
+    rc = run_quantize(X, px, &cfg, Xq_ctx, part_x, st);
+    if (rc) return rc;
+    rc = run_quantize(W, pw, &cfg, Wq_ctx, part_w, st);
+    if (rc) return rc;
+    return run_gemm(Xq_ctx, Wq_ctx, Y, out_dtype, gws, gbytes, st);
+}
+
+int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D, int64_t C, void *dX,
+                        int out_dtype, uint64_t seed, uint32_t layer_id, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!dY || !Wq_ctx) return NVFP4_ERR_NULL;
+    if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
+    if (C % 64 != 0) return NVFP4_ERR_SHAPE;
+    int rc = check_out(dX, out_dtype);
+    if (rc) return rc;
+    if (Wq_ctx->rows != C || Wq_ctx->K != D) return NVFP4_ERR_MISMATCH;
+    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD_DX, N, D, C, NVFP4_OUTER_TENSOR))
+        return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
+    Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
+    float *part = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
+    nvfp4_tensor dYq{}, Wq2{};
+    if (!carve_tensor(cv, N, C, &dYq) || !carve_tensor(cv, D, C, &Wq2)) return NVFP4_ERR_WORKSPACE;
+    const size_t gbytes = gemm_workspace_bytes(N, D, C);
+    void *gws = gbytes ? cv.take(gbytes) : nullptr;
+
+    nvfp4_qcfg c3{};
+    c3.rounding = NVFP4_ROUND_SR;
+    c3.outer_mode = NVFP4_OUTER_TENSOR;
+    c3.seed = seed;
+    c3.tensor_id = layer_id * 8u + 3u;
+    nvfp4_qcfg c4 = c3;
+    c4.tensor_id = layer_id * 8u + 4u;
+    QuantPlan p3{}, p4{};
+    rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 0, &c3, &dYq, &p3);
+    if (rc) return rc;
+    rc = plan_quantize(Wq_ctx, NVFP4_SRC_NVFP4, C, D, 1, &c4, &Wq2, &p4);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = run_quantize(dY, p3, &c3, &dYq, part, st);
+    if (rc) return rc;
+    rc = run_quantize(Wq_ctx, p4, &c4, &Wq2, nullptr, st);
+    if (rc) return rc;
+    return run_gemm(&dYq, &Wq2, dX, out_dtype, gws, gbytes, st);
+}
+
+int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C, void *dW,
+                        int out_dtype, uint64_t seed, uint32_t layer_id, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!dY || !Xq_ctx) return NVFP4_ERR_NULL;
+    if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
+    if (N % 64 != 0) return NVFP4_ERR_SHAPE;
+    int rc = check_out(dW, out_dtype);
+    if (rc) return rc;
+    if (Xq_ctx->rows != N || Xq_ctx->K != D) return NVFP4_ERR_MISMATCH;
+    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD_DW, N, D, C, NVFP4_OUTER_TENSOR))
+        return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
+    Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
+    float *part = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
+    nvfp4_tensor dYq{}, Xq2{};
+    if (!carve_tensor(cv, C, N, &dYq) || !carve_tensor(cv, D, N, &Xq2)) return NVFP4_ERR_WORKSPACE;
+    const size_t gbytes = gemm_workspace_bytes(C, D, N);
+    void *gws = gbytes ? cv.take(gbytes) : nullptr;
+
+    nvfp4_qcfg c5{};
+    c5.rounding = NVFP4_ROUND_SR;
+    c5.outer_mode = NVFP4_OUTER_TENSOR;
+    c5.seed = seed;
+    c5.tensor_id = layer_id * 8u + 5u;
+    nvfp4_qcfg c6 = c5;
+    c6.tensor_id = layer_id * 8u + 6u;
+    QuantPlan p5{}, p6{};
+    rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 1, &c5, &dYq, &p5);
+    if (rc) return rc;
+    rc = plan_quantize(Xq_ctx, NVFP4_SRC_NVFP4, N, D, 1, &c6, &Xq2, &p6);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = run_quantize(dY, p5, &c5, &dYq, part, st);
+    if (rc) return rc;
+    rc = run_quantize(Xq_ctx, p6, &c6, &Xq2, nullptr, st);
+    if (rc) return rc;
+    return run_gemm(&dYq, &Xq2, dW, out_dtype, gws, gbytes, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,148 @@
+// Device-side number-format helpers for the NVFP4 kernels (gfx950).
+//
+// E2M1 / E4M3 / double-block arithmetic of TetraJet-v2 Sec. 2.1-2.2, written as
+// bit manipulation on binary32.  Everything that decides a code is plain IEEE
+// binary32 with one rounding per operation (the translation unit is compiled with
+// -ffp-contract=off and subnormals enabled).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tj {
+
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+
+// ---- lane exchange inside a row of 16 lanes (DPP) -------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int DPP_ROW_HALF_MIRROR = 0x141; // lane i <-> 7-i inside 8
+constexpr int DPP_ROW_MIRROR = 0x140;      // lane i <-> 15-i inside 16
+constexpr int DPP_ROW_SHL2 = 0x102;        // lane i reads lane i+2
+constexpr int DPP_ROW_SHL4 = 0x104;        // lane i reads lane i+4
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---- E4M3 (bias 7, no infinity, max 448 = 0x7E, subnormals k * 2^-9) ------------------------
+
+// value of a code: the 7 payload bits sit where binary32 keeps exponent and top mantissa
+// bits once shifted by 20; the 2^120 factor re-biases (127 - 7) and normalises subnormals.
+__device__ __forceinline__ float e4m3_value(uint32_t code) { return u2f(code << 20) * 0x1p120f; }
+
+// round a non-negative binary32 to the nearest code, ties to the even code, saturating
+__device__ __forceinline__ uint32_t e4m3_round_ne(float s)
+{
+    uint32_t b = f2u(s);
+    uint32_t rn = (b + 0x7FFFFu + ((b >> 20) & 1u)) >> 20;     // round mantissa to 3 bits
+    int cn = (int)rn - (120 << 3);
+    cn = cn > 0x7E ? 0x7E : cn;
+    uint32_t cs = f2u(s + 16384.0f) & 0xFFu;                   // below 2^-6: multiples of 2^-9
+    return s < 0x1p-6f ? cs : (uint32_t)cn;
+}
+
+// smallest code whose value is >= s, saturating
+__device__ __forceinline__ uint32_t e4m3_round_up(float s)
+{
+    uint32_t b = f2u(s);
+    int cn = (int)((b + 0xFFFFFu) >> 20) - (120 << 3);
+    cn = cn > 0x7E ? 0x7E : cn;
+    uint32_t cs = (uint32_t)ceilf(s * 512.0f);
+    return s < 0x1p-6f ? cs : (uint32_t)cn;
+}
+
+template <bool UP>
+__device__ __forceinline__ uint32_t e4m3_round(float s) { return UP ? e4m3_round_up(s) : e4m3_round_ne(s); }
+
+// ---- E2M1 -----------------------------------------------------------------------------------
+
+// value of a 3-bit magnitude code: E2M1 is a tiny IEEE format (bias 1, subnormal 0.5)
+__device__ __forceinline__ float e2m1_value(uint32_t m) { return u2f(m << 22) * 0x1p126f; }
+
+// Sec. 2.1 deterministic rounding of y: nearest value, ties to the even code, |y| clamped to 6;
+// returns sign<<3 | magnitude code, the sign being y's sign bit
+__device__ __forceinline__ uint32_t e2m1_rtn(float y)
+{
+    float a = fminf(fabsf(y), 6.0f);
+    uint32_t b = f2u(fmaxf(a, 1.0f));
+    uint32_t hi = (b + 0x1FFFFFu + ((b >> 22) & 1u)) >> 22;    // 254 (a <= 1) .. 259 (a = 6)
+    uint32_t lo = (a > 0.25f ? 1u : 0u) + (a >= 0.75f ? 1u : 0u);
+    return (hi + lo - 254u) | ((f2u(y) >> 28) & 8u);
+}
+
+// Sec. 2.1 stochastic rounding of y with 16 uniform bits u: scaled by 2^-126 the value's
+// binary32 pattern is the E2M1 pattern extended by 22 fraction bits (fixed point below 1),
+// so adding u at bit 6 and truncating rounds up with probability floor(frac * 2^16) / 2^16.
+__device__ __forceinline__ uint32_t e2m1_sr(float y, uint32_t u16)
+{
+    float a = fminf(fabsf(y), 6.0f);
+    uint32_t w = f2u(a * 0x1p-126f) + (u16 << 6);
+    return (w >> 22) | ((f2u(y) >> 28) & 8u);
+}
+
+// ---- stochastic-rounding bit generator --------------------------------------------------------
+
+// 32 bits for the element pair p of a stream keyed by (k0, k1): two rounds of
+// xorshift-multiply with the second key word folded in between
+__device__ __forceinline__ uint32_t pair_bits(uint32_t p, uint32_t k0, uint32_t k1)
+{
+    uint32_t h = p + k0;
+    h ^= h >> 16;
+    h *= 0x7FEB352Du;
+    h = h ^ (h >> 15) ^ k1;
+    h *= 0x846CA68Bu;
+    h ^= h >> 16;
+    return h;
+}
+
+// ---- outer scale (Sec. 2.2, S_global) ---------------------------------------------------------
+
+struct OuterScale {
+    float S_g;     // amax / (448*6), floored at 2^-100; 1 for an all-zero group
+    float inv_sg;  // 1 / S_g
+    float inv_cg;  // (1 / S_g) * (1/6)
+};
+
+__device__ __forceinline__ OuterScale outer_scale(float amax)
+{
+    OuterScale o;
+    float q = amax / 2688.0f;
+    q = fmaxf(q, 0x1p-100f);
+    o.S_g = amax == 0.0f ? 1.0f : q;
+    o.inv_sg = 1.0f / o.S_g;
+    o.inv_cg = o.inv_sg * (1.0f / 6.0f);
+    return o;
+}
+
+// bf16 pair -> two binary32
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return u2f(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return u2f(w & 0xFFFF0000u); }
+
+__device__ __forceinline__ ushort2_t as_us2(uint32_t w) { return __builtin_bit_cast(ushort2_t, w); }
+__device__ __forceinline__ uint32_t as_u32(ushort2_t v) { return __builtin_bit_cast(uint32_t, v); }
+
+// max |.| of the 8 bf16 in v, as the bf16 bit pattern (finite inputs order like integers)
+__device__ __forceinline__ uint32_t absmax8_bits(uint4 v)
+{
+    ushort2_t a = as_us2(v.x & 0x7FFF7FFFu), b = as_us2(v.y & 0x7FFF7FFFu);
+    ushort2_t c = as_us2(v.z & 0x7FFF7FFFu), d = as_us2(v.w & 0x7FFF7FFFu);
+    ushort2_t m = __builtin_elementwise_max(__builtin_elementwise_max(a, b), __builtin_elementwise_max(c, d));
+    return m.x > m.y ? m.x : m.y;
+}
+
+}  // namespace tj

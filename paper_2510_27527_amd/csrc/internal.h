@@ -1,0 +1,71 @@
+// Host-side launcher interfaces between the C-ABI layer (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tj {
+
+constexpr int kMaxAmaxPartials = 512;   // floats of workspace one tensor-maximum reduction uses
+
+struct QuantOut {
+    uint8_t *codes;
+    uint8_t *scales;
+    float *gscale;
+    float *amax_deq;   // may be null
+};
+
+struct QuantParams {
+    int rounding;      // 0 RTN, 1 SR
+    int scale_up;      // 0 nearest-even, 1 upward
+    int outer;         // 0 tensor, 1 block128
+    uint32_t k0, k1;   // stream key words
+    // tensor maximum: either a device scalar, or `npart` partial maxima
+    const float *amax_scalar;
+    const float *amax_partials;
+    int npart;
+};
+
+// view of an NVFP4 source tensor [R x C] (grouped along C)
+struct PackedSrc {
+    const uint8_t *codes;
+    const uint8_t *scales;
+    const float *gscale;
+    int outer;
+};
+
+// partial maxima of |x| over a bf16 array of n elements (n % 8 == 0); returns the number of partials written
+int launch_amax_partials(const void *src, int64_t n, float *partials, hipStream_t st);
+// reduce partials to one scalar
+void launch_amax_final(const float *partials, int npart, float *out, hipStream_t st);
+// zero one float
+void launch_zero_scalar(float *p, hipStream_t st);
+
+// row-wise quantization of a bf16 [rows x K] array (groups along K)
+hipError_t launch_quant_row_bf16(const void *src, int64_t rows, int64_t K, const QuantParams &p, const QuantOut &o,
+                                 hipStream_t st);
+// column-wise quantization of a bf16 [R x C] array: output [C x R] grouped along R
+hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
+                                 hipStream_t st);
+// column-wise re-quantization of an NVFP4 [R x C] tensor: output [C x R] grouped along R
+hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
+                              hipStream_t st);
+// row-wise re-quantization of an NVFP4 [R x C] tensor (same grouping axis)
+hipError_t launch_requant_row(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
+                              hipStream_t st);
+
+struct GemmOperand {
+    const uint8_t *codes;
+    const uint8_t *scales;
+    const float *gscale;   // tensor-mode scalar
+    int64_t rows;
+};
+
+// Out[M x N] = A[M x K] * B[N x K]^T; splitk_ws holds split * M * N floats when split > 1
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K, void *out, int out_f32,
+                          void *ws, size_t ws_bytes, hipStream_t st);
+
+uint64_t stream_key(uint64_t seed, uint32_t tensor_id);
+
+}  // namespace tj

@@ -1,0 +1,410 @@
+// NVFP4 double-block quantizer kernels for gfx950 (TetraJet-v2 Sec. 2.1-2.2, the six
+// quantizers of Sec. 2.3).  All of them are bandwidth-bound streaming kernels:
+//   amax_partials   per-tensor max|x| of a bf16 array (TENSOR outer mode only)
+//   quant_row       groups of 16 along the contiguous axis; 8 elements (one 128-bit load) per
+//                   lane, two lanes per group, group maximum exchanged by DPP
+//   quant_col       groups of 16 down the columns: a 128 x 64 tile goes through LDS (rotated so
+//                   both the 128-bit row writes and the per-column reads are conflict free), each
+//                   lane then owns two columns x 16 rows; the output is the transposed operand
+//   requant_col     same, the source being a packed NVFP4 tensor (Q4 / Q6)
+#include "device_fmt.h"
+#include "internal.h"
+
+namespace tj {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowIter = 8;    // 128-bit chunks per thread in the row kernel
+
+struct KArgs {
+    uint32_t *codes;
+    uint8_t *scales;
+    float *gscale;
+    float *amax_deq;
+    const float *amax_scalar;
+    const float *amax_partials;
+    int npart;
+    uint32_t k0, k1;
+};
+
+// tensor maximum for this workgroup: a scalar, or the maximum of the partials
+__device__ __forceinline__ float block_tensor_amax(const KArgs &a, float *red)
+{
+    if (a.amax_scalar) return a.amax_scalar[0];
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < a.npart; i += kThreads) m = fmaxf(m, a.amax_partials[i]);
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// reciprocals of all E4M3 values (entry 0 = 0, so a zero scale gives all-zero codes)
+__device__ __forceinline__ void fill_inv_table(float *tab)
+{
+    if (threadIdx.x < 128) {
+        float v = e4m3_value(threadIdx.x);
+        tab[threadIdx.x] = (threadIdx.x == 0 || threadIdx.x == 127) ? 0.0f : 1.0f / v;
+    }
+}
+
+// eight consecutive elements of one group -> eight codes in one dword (element 0 in the low nibble)
+template <int ROUND>
+__device__ __forceinline__ uint32_t quant8(const float (&x)[8], float r, uint32_t pair0, uint32_t k0, uint32_t k1)
+{
+    uint32_t out = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float y0 = x[2 * j] * r, y1 = x[2 * j + 1] * r;
+        uint32_t c0, c1;
+        if (ROUND == 0) {
+            c0 = e2m1_rtn(y0);
+            c1 = e2m1_rtn(y1);
+        } else {
+            uint32_t h = pair_bits(pair0 + j, k0, k1);
+            c0 = e2m1_sr(y0, h & 0xFFFFu);
+            c1 = e2m1_sr(y1, h >> 16);
+        }
+        out |= (c0 | (c1 << 4)) << (8 * j);
+    }
+    return out;
+}
+
+__device__ __forceinline__ void publish_deq_max(float v, float *dst)
+{
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<unsigned int *>(dst), f2u(v));
+}
+
+// ------------------------------------------------------------------------------- amax ----
+
+__global__ __launch_bounds__(kThreads) void amax_partials_kernel(const uint4 *__restrict__ src, int64_t nchunks,
+                                                                 float *__restrict__ partials)
+{
+    __shared__ float red[4];
+    ushort2_t m = {0, 0};
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; c + 3 * stride < nchunks; c += 4 * stride) {
+        uint4 v0 = src[c], v1 = src[c + stride], v2 = src[c + 2 * stride], v3 = src[c + 3 * stride];
+        uint32_t a = absmax8_bits(v0), b = absmax8_bits(v1), d = absmax8_bits(v2), e = absmax8_bits(v3);
+        uint32_t ab = a > b ? a : b, de = d > e ? d : e;
+        uint32_t q = ab > de ? ab : de;
+        m.x = m.x > q ? m.x : (unsigned short)q;
+    }
+    for (; c < nchunks; c += stride) {
+        uint32_t q = absmax8_bits(src[c]);
+        m.x = m.x > q ? m.x : (unsigned short)q;
+    }
+    float f = wave_max(u2f((uint32_t)m.x << 16));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = f;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+__global__ __launch_bounds__(kThreads) void amax_final_kernel(const float *__restrict__ partials, int npart,
+                                                              float *__restrict__ out)
+{
+    __shared__ float red[4];
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < npart; i += kThreads) m = fmaxf(m, partials[i]);
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+__global__ void zero_scalar_kernel(float *p) { p[0] = 0.0f; }
+
+// ---------------------------------------------------------------------------- row-wise ----
+
+template <int ROUND, bool SUP, int OUTER, bool DEQ>
+__global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__restrict__ src, int64_t nchunks, KArgs a)
+{
+    __shared__ float inv_tab[128];
+    __shared__ float red[4];
+    const int tid = threadIdx.x;
+    fill_inv_table(inv_tab);
+    OuterScale os;
+    if (OUTER == 0) {
+        os = outer_scale(block_tensor_amax(a, red));
+        if (blockIdx.x == 0 && tid == 0) a.gscale[0] = os.S_g;
+    }
+    __syncthreads();
+    float deq = 0.0f;
+#pragma unroll 2
+    for (int it = 0; it < kRowIter; ++it) {
+        const int64_t c = ((int64_t)blockIdx.x * kRowIter + it) * kThreads + tid;
+        const bool valid = c < nchunks;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (valid) v = src[c];
+        const uint32_t hm = absmax8_bits(v);
+        const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
+        const uint32_t bm = hm > o1 ? hm : o1;
+        if (OUTER == 1) {
+            uint32_t gm = bm, t;
+            t = dpp<DPP_QUAD_XOR2>(gm);       gm = gm > t ? gm : t;
+            t = dpp<DPP_ROW_HALF_MIRROR>(gm); gm = gm > t ? gm : t;
+            t = dpp<DPP_ROW_MIRROR>(gm);      gm = gm > t ? gm : t;
+            os = outer_scale(u2f(gm << 16));
+            if (valid && (tid & 15) == 0) a.gscale[c >> 4] = os.S_g;
+        }
+        const float amax_b = u2f(bm << 16);
+        const float s = amax_b * os.inv_cg;
+        const uint32_t sc = e4m3_round<SUP>(s);
+        const float r = os.inv_sg * inv_tab[sc];
+        const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                            bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+        const uint32_t q = quant8<ROUND>(x, r, (uint32_t)(c * 4), a.k0, a.k1);
+        if (valid) a.codes[c] = q;
+        // four scale bytes (lanes c, c+2, c+4, c+6) travel to the lane with c % 8 == 0
+        const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
+        const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
+        if (valid && (tid & 7) == 0) {
+            if (c + 8 <= nchunks) {
+                reinterpret_cast<uint32_t *>(a.scales)[c >> 3] = s4;
+            } else {
+                for (int b = 0; b < 4; ++b)
+                    if (c + 2 * b < nchunks) a.scales[(c >> 1) + b] = (uint8_t)(s4 >> (8 * b));
+            }
+        }
+        if (DEQ) {
+            // the group's largest element gets the group's largest code (rounding is monotone)
+            const uint32_t mm = e2m1_rtn(amax_b * r) & 7u;
+            float val = e2m1_value(mm) * e4m3_value(sc);
+            if (OUTER == 1) val = val * os.S_g;
+            deq = fmaxf(deq, val);
+        }
+    }
+    if (DEQ) {
+        if (OUTER == 0) deq = deq * os.S_g;
+        publish_deq_max(deq, a.amax_deq);
+    }
+}
+
+// ------------------------------------------------------------------------- column-wise ----
+
+constexpr int kTileR = 128;   // source rows per tile = 8 groups of 16
+constexpr int kTileC = 64;    // source columns per tile = 32 dwords of bf16 pairs
+
+struct ColArgs {
+    const uint4 *src;          // bf16 source
+    const uint8_t *src_codes;  // packed source
+    const uint8_t *src_scales;
+    const float *src_gscale;
+    int64_t R, C;
+    KArgs k;
+};
+
+// dword column of the tile, rotated by 4 per 16 rows
+__device__ __forceinline__ int tile_pos(int row, int dwcol) { return row * 32 + ((dwcol + 4 * (row >> 4)) & 31); }
+
+// 16 packed codes of one source group times its scale, as 8 dwords of bf16 pairs (exact)
+__device__ __forceinline__ void decode_group_bf16(uint2 codes, uint32_t sc, uint32_t (&out)[8])
+{
+    const float sb = e4m3_value(sc);
+    const uint32_t w[2] = {codes.x, codes.y};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t byte = (w[i >> 2] >> (8 * (i & 3))) & 0xFFu;
+        const float lo = e2m1_value(byte & 7u) * sb;
+        const float hi = e2m1_value((byte >> 4) & 7u) * sb;
+        const uint32_t lob = (f2u(lo) >> 16) | ((byte & 8u) << 12);
+        const uint32_t hib = (f2u(hi) & 0xFFFF0000u) | ((byte & 0x80u) << 24);
+        out[i] = lob | hib;
+    }
+}
+
+template <int ROUND, bool SUP, bool PACKED>
+__global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t tile[kTileR * 32];
+    __shared__ float inv_tab[128];
+    __shared__ float red[4];
+    const int tid = threadIdx.x;
+    const int64_t R = a.R, C = a.C;
+    const int64_t R0 = (int64_t)blockIdx.y * kTileR, C0 = (int64_t)blockIdx.x * kTileC;
+    fill_inv_table(inv_tab);
+
+    // phase 1: tile -> LDS as bf16 pairs, row-major with rotated columns
+    if (!PACKED) {
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int row = pass * 32 + (tid >> 3), q = tid & 7;
+            const int64_t gr = R0 + row, gc = C0 + q * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (gr < R && gc < C) v = a.src[(gr * C + gc) >> 3];
+            *reinterpret_cast<uint4 *>(&tile[tile_pos(row, q * 4)]) = v;
+        }
+    } else {
+        const int row = tid >> 1, half = tid & 1;
+        const int64_t gr = R0 + row;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int64_t gc = C0 + 32 * half + 16 * b;
+            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (gr < R && gc < C) {
+                const uint2 cw = *reinterpret_cast<const uint2 *>(a.src_codes + ((gr * C + gc) >> 1));
+                const uint32_t sc = a.src_scales[(gr * C + gc) >> 4];
+                decode_group_bf16(cw, sc, d);
+            }
+            const int dw = 16 * half + 8 * b;
+            *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw)]) = make_uint4(d[0], d[1], d[2], d[3]);
+            *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw + 4)]) = make_uint4(d[4], d[5], d[6], d[7]);
+        }
+    }
+    const OuterScale os = outer_scale(block_tensor_amax(a.k, red));
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) a.k.gscale[0] = os.S_g;
+    const float src_sg = PACKED ? a.src_gscale[0] : 1.0f;
+    __syncthreads();
+
+    // phase 2: lane = (row group rb, column pair cp): 16 dwords down two columns
+    const int rb = tid & 7, cp = tid >> 3;
+    uint32_t w[16];
+    ushort2_t m2 = {0, 0};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        w[i] = tile[tile_pos(16 * rb + i, cp)];
+        m2 = __builtin_elementwise_max(m2, as_us2(w[i] & 0x7FFF7FFFu));
+    }
+    const int64_t k_first = R0 + 16 * rb;
+    if (k_first >= R) return;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t c = C0 + 2 * cp + j;
+        if (c >= C) break;
+        float amax_b = u2f((uint32_t)(j == 0 ? m2.x : m2.y) << 16);
+        if (PACKED) amax_b = amax_b * src_sg;
+        const float s = amax_b * os.inv_cg;
+        const uint32_t sc = e4m3_round<SUP>(s);
+        const float r = os.inv_sg * inv_tab[sc];
+        float x0[8], x1[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            x0[i] = j == 0 ? bf16_lo(w[i]) : bf16_hi(w[i]);
+            x1[i] = j == 0 ? bf16_lo(w[8 + i]) : bf16_hi(w[8 + i]);
+            if (PACKED) { x0[i] = x0[i] * src_sg; x1[i] = x1[i] * src_sg; }
+        }
+        const uint32_t pair0 = (uint32_t)((c * R + k_first) >> 1);
+        uint2 q;
+        q.x = quant8<ROUND>(x0, r, pair0, a.k.k0, a.k.k1);
+        q.y = quant8<ROUND>(x1, r, pair0 + 4, a.k.k0, a.k.k1);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(a.k.codes) + ((c * R + k_first) >> 1)) = q;
+        a.k.scales[(c * R + k_first) >> 4] = (uint8_t)sc;
+    }
+}
+
+KArgs make_kargs(const QuantParams &p, const QuantOut &o)
+{
+    KArgs k;
+    k.codes = reinterpret_cast<uint32_t *>(o.codes);
+    k.scales = o.scales;
+    k.gscale = o.gscale;
+    k.amax_deq = o.amax_deq;
+    k.amax_scalar = p.amax_scalar;
+    k.amax_partials = p.amax_partials;
+    k.npart = p.npart;
+    k.k0 = p.k0;
+    k.k1 = p.k1;
+    return k;
+}
+
+template <int ROUND, bool SUP, int OUTER>
+void launch_row_t(const void *src, int64_t nchunks, const KArgs &k, bool deq, hipStream_t st)
+{
+    const int64_t per_wg = (int64_t)kThreads * kRowIter;
+    const unsigned grid = (unsigned)((nchunks + per_wg - 1) / per_wg);
+    if (deq)
+        hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, OUTER, true>), dim3(grid), dim3(kThreads), 0, st,
+                           reinterpret_cast<const uint4 *>(src), nchunks, k);
+    else
+        hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, OUTER, false>), dim3(grid), dim3(kThreads), 0, st,
+                           reinterpret_cast<const uint4 *>(src), nchunks, k);
+}
+
+template <bool PACKED>
+void launch_col_t(const ColArgs &a, int rounding, int scale_up, hipStream_t st)
+{
+    dim3 grid((unsigned)((a.C + kTileC - 1) / kTileC), (unsigned)((a.R + kTileR - 1) / kTileR));
+    if (rounding == 0) {
+        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<0, true, PACKED>), grid, dim3(kThreads), 0, st, a);
+        else          hipLaunchKernelGGL((quant_col_kernel<0, false, PACKED>), grid, dim3(kThreads), 0, st, a);
+    } else {
+        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<1, true, PACKED>), grid, dim3(kThreads), 0, st, a);
+        else          hipLaunchKernelGGL((quant_col_kernel<1, false, PACKED>), grid, dim3(kThreads), 0, st, a);
+    }
+}
+
+}  // namespace
+
+int launch_amax_partials(const void *src, int64_t n, float *partials, hipStream_t st)
+{
+    const int64_t nchunks = n / 8;
+    int64_t want = (nchunks + (int64_t)kThreads * 8 - 1) / ((int64_t)kThreads * 8);
+    int grid = (int)(want < 1 ? 1 : (want > kMaxAmaxPartials ? kMaxAmaxPartials : want));
+    hipLaunchKernelGGL(amax_partials_kernel, dim3(grid), dim3(kThreads), 0, st,
+                       reinterpret_cast<const uint4 *>(src), nchunks, partials);
+    return grid;
+}
+
+void launch_amax_final(const float *partials, int npart, float *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(amax_final_kernel, dim3(1), dim3(kThreads), 0, st, partials, npart, out);
+}
+
+void launch_zero_scalar(float *p, hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_scalar_kernel, dim3(1), dim3(1), 0, st, p);
+}
+
+hipError_t launch_quant_row_bf16(const void *src, int64_t rows, int64_t K, const QuantParams &p, const QuantOut &o,
+                                 hipStream_t st)
+{
+    const int64_t nchunks = rows * K / 8;
+    if (nchunks == 0) return hipSuccess;
+    const KArgs k = make_kargs(p, o);
+    const bool deq = o.amax_deq != nullptr && p.rounding == 0;
+    const int sel = (p.rounding << 2) | (p.scale_up << 1) | p.outer;
+    switch (sel) {
+        case 0: launch_row_t<0, false, 0>(src, nchunks, k, deq, st); break;
+        case 1: launch_row_t<0, false, 1>(src, nchunks, k, deq, st); break;
+        case 2: launch_row_t<0, true, 0>(src, nchunks, k, deq, st); break;
+        case 3: launch_row_t<0, true, 1>(src, nchunks, k, deq, st); break;
+        case 4: launch_row_t<1, false, 0>(src, nchunks, k, false, st); break;
+        case 5: launch_row_t<1, false, 1>(src, nchunks, k, false, st); break;
+        case 6: launch_row_t<1, true, 0>(src, nchunks, k, false, st); break;
+        default: launch_row_t<1, true, 1>(src, nchunks, k, false, st); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
+                                 hipStream_t st)
+{
+    if (R == 0 || C == 0) return hipSuccess;
+    ColArgs a{};
+    a.src = reinterpret_cast<const uint4 *>(src);
+    a.R = R;
+    a.C = C;
+    a.k = make_kargs(p, o);
+    launch_col_t<false>(a, p.rounding, p.scale_up, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
+                              hipStream_t st)
+{
+    if (R == 0 || C == 0) return hipSuccess;
+    ColArgs a{};
+    a.src_codes = src.codes;
+    a.src_scales = src.scales;
+    a.src_gscale = src.gscale;
+    a.R = R;
+    a.C = C;
+    a.k = make_kargs(p, o);
+    launch_col_t<true>(a, p.rounding, p.scale_up, st);
+    return hipGetLastError();
+}
+
+}  // namespace tj

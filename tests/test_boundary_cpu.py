@@ -1,0 +1,124 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_27527_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000      # a 16-byte aligned, never dereferenced "device pointer"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2510_27527_amd import build
+        build.build(force=True)
+    return B.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "tjnvfp4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nvfp4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert {"nvfp4_quantize", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_version_and_strerror(lib):
+    assert b"gfx950" in lib.nvfp4_version()
+    for code in range(0, -8, -1):
+        assert lib.nvfp4_strerror(code) not in (None, b"unknown error code")
+    assert lib.nvfp4_strerror(-99) == b"unknown error code"
+
+
+def _tensor(rows=0, K=0, outer=0, amax=FAKE):
+    return B.CTensor(FAKE, FAKE + 0x1000, FAKE + 0x2000, amax, rows, K, outer, 0)
+
+
+def _quant(lib, src=FAKE, kind=0, R=32, Cc=64, axis=0, cfg=None, out=None, ws=FAKE, ws_bytes=1 << 20):
+    cfg = cfg or B.CQcfg(0, 0, 0, 0, 0, None)
+    out = out or _tensor()
+    return lib.nvfp4_quantize(src, kind, R, Cc, axis, C.byref(cfg), C.byref(out), ws, ws_bytes, None)
+
+
+def test_quantize_rejects_bad_arguments(lib):
+    assert _quant(lib, src=None) == -1
+    assert lib.nvfp4_quantize(FAKE, 0, 32, 64, 0, None, C.byref(_tensor()), FAKE, 1 << 20, None) == -1
+    assert _quant(lib, out=B.CTensor(None, FAKE, FAKE, None, 0, 0, 0, 0)) == -1
+    assert _quant(lib, Cc=24) == -2                       # K % 16
+    assert _quant(lib, R=24, Cc=64, axis=1) == -2         # K = R % 16
+    assert _quant(lib, R=32, Cc=20, axis=1) == -2         # C % 8 for column-wise loads
+    assert _quant(lib, R=-1) == -2
+    assert _quant(lib, R=1 << 20, Cc=1 << 20) == -2       # > 2^33 elements
+    assert _quant(lib, Cc=64, cfg=B.CQcfg(0, 0, 1, 0, 0, None)) == -2     # BLOCK128 needs K % 128
+    assert _quant(lib, kind=5) == -3
+    assert _quant(lib, axis=2) == -3
+    assert _quant(lib, cfg=B.CQcfg(7, 0, 0, 0, 0, None)) == -3
+    assert _quant(lib, cfg=B.CQcfg(0, 9, 0, 0, 0, None)) == -3
+    assert _quant(lib, cfg=B.CQcfg(0, 0, 4, 0, 0, None)) == -3
+    assert _quant(lib, ws=None) == -4
+    assert _quant(lib, ws_bytes=16) == -4
+    assert _quant(lib, src=FAKE + 2) == -5
+    assert _quant(lib, out=B.CTensor(FAKE + 1, FAKE, FAKE, None, 0, 0, 0, 0)) == -5
+    # NVFP4 source: descriptor must match R, C and carry the maximum
+    src = _tensor(32, 64, 0)
+    cfg = B.CQcfg(1, 0, 0, 0, 0, None)
+    call = lambda s, R, Cc, axis: lib.nvfp4_quantize(C.cast(C.pointer(s), C.c_void_p), 1, R, Cc, axis, C.byref(cfg),
+                                                     C.byref(_tensor()), FAKE, 1 << 20, None)
+    assert call(src, 32, 128, 1) == -6
+    assert call(_tensor(32, 64, 0, amax=None), 32, 64, 1) == -1
+    assert call(src, 32, 64, 0) == -3                     # same-axis re-quantization is not provided
+
+
+def test_gemm_and_linear_reject_bad_arguments(lib):
+    A, Bt = _tensor(128, 256), _tensor(64, 256)
+    g = lambda a, b, out=FAKE, dt=0, ws=FAKE, wsb=1 << 30: lib.nvfp4_gemm_nt(C.byref(a), C.byref(b), out, dt, ws, wsb, None)
+    assert g(A, _tensor(64, 128)) == -6
+    assert g(_tensor(128, 80), _tensor(64, 80)) == -2      # K % 64
+    assert g(_tensor(128, 256, outer=1), Bt) == -3
+    assert g(A, Bt, out=None) == -1
+    assert g(A, Bt, dt=3) == -3
+    assert g(A, Bt, out=FAKE + 4) == -5
+    big_a, big_b = _tensor(64, 16384), _tensor(64, 16384)   # split-K needs scratch
+    assert lib.nvfp4_workspace_bytes(B.OP_GEMM, 64, 16384, 64, 0) > 0
+    assert g(big_a, big_b, ws=None, wsb=0) == -4
+
+    fwd = lambda N, D, Cc, ws=FAKE, wsb=1 << 40, outer=0: lib.nvfp4_linear_fwd(
+        FAKE, FAKE, N, D, Cc, FAKE, 0, C.byref(_tensor()), C.byref(_tensor()), outer, ws, wsb, None)
+    assert fwd(128, 100, 64) == -2
+    assert fwd(128, 128, 64, outer=1) == -3
+    assert fwd(128, 128, 64, wsb=8) == -4
+    assert fwd(-1, 128, 64) == -2
+    W = _tensor(64, 128)
+    dx = lambda N, D, Cc, w=W, wsb=1 << 40: lib.nvfp4_linear_bwd_dx(FAKE, C.byref(w), N, D, Cc, FAKE, 0, 0, 0, FAKE, wsb, None)
+    assert dx(128, 128, 32) == -2                          # C % 64
+    assert dx(128, 256, 64) == -6
+    assert dx(128, 128, 64, wsb=100) == -4
+    X = _tensor(128, 128)
+    dw = lambda N, D, Cc, x=X, wsb=1 << 40: lib.nvfp4_linear_bwd_dw(FAKE, C.byref(x), N, D, Cc, FAKE, 0, 0, 0, FAKE, wsb, None)
+    assert dw(96, 128, 64) == -2                           # N % 64
+    assert dw(128, 64, 64) == -6
+    assert dw(128, 128, 64, wsb=100) == -4
+
+
+def test_workspace_sizes(lib):
+    assert lib.nvfp4_workspace_bytes(99, 1, 1, 1, 0) == 0
+    q = lib.nvfp4_workspace_bytes(B.OP_QUANTIZE, 8192, 8192, 0, 0)
+    assert 0 < q <= 4096
+    dx = lib.nvfp4_workspace_bytes(B.OP_LINEAR_BWD_DX, 8192, 768, 3072, 0)
+    assert dx >= (8192 * 3072 + 768 * 3072) * 9 // 16
+
+
+def test_stream_key_is_a_function_of_seed_and_id(lib):
+    ks = {lib.nvfp4_stream_key(s, t) for s in range(8) for t in range(8)}
+    assert len(ks) == 64

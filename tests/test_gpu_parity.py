@@ -1,0 +1,308 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bar: codes, E4M3 scale bytes, FP32 outer scales and stochastic-rounding outcomes are bit-exact;
+matrix products satisfy |c - ref| <= 1e-3 |ref| + 1e-6 sum_k |a||b| on the FP32 output (the
+second term covers cancellation) and 2^-8 |ref| + the same floor on the bf16 output (bf16
+rounding alone is up to 2^-9 relative).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+tj = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _load():
+    global tj
+    import paper_2510_27527_amd as mod
+    tj = mod
+    mod.binding.lib()          # fails loudly if the HIP library is missing
+    yield
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_dev(q: oracle.NVFP4):
+    t = tj.alloc_nvfp4(q.rows, q.K, q.outer)
+    t.codes.copy_(torch.from_numpy(q.codes))
+    t.scales.copy_(torch.from_numpy(q.scales))
+    t.gscale.copy_(torch.from_numpy(q.gscale))
+    t.amax_deq.fill_(q.amax_deq)
+    return t
+
+
+def assert_same(q_gpu, q_ref: oracle.NVFP4, what="", check_amax=False):
+    torch.cuda.synchronize()
+    assert (q_gpu.rows, q_gpu.K) == (q_ref.rows, q_ref.K), what
+    gs = q_gpu.gscale.cpu().numpy()
+    assert np.array_equal(gs.view(np.uint32).ravel(), q_ref.gscale.view(np.uint32).ravel()), what + " gscale"
+    sc = q_gpu.scales.cpu().numpy()
+    bad = np.argwhere(sc != q_ref.scales)
+    assert len(bad) == 0, "%s scales differ at %s (%d total)" % (what, bad[:5].tolist(), len(bad))
+    cd = q_gpu.codes.cpu().numpy()
+    bad = np.argwhere(cd != q_ref.codes)
+    assert len(bad) == 0, "%s codes differ at %s (%d total): gpu %s ref %s" % (
+        what, bad[:5].tolist(), len(bad), cd[tuple(bad[0])] if len(bad) else None,
+        q_ref.codes[tuple(bad[0])] if len(bad) else None)
+    if check_amax:
+        a = float(q_gpu.amax_deq.cpu().numpy()[0])
+        assert np.float32(a) == np.float32(q_ref.amax_deq), (what, a, q_ref.amax_deq)
+
+
+def check_product(got: torch.Tensor, ref: np.ndarray, absref: np.ndarray, what=""):
+    g = got.double().cpu().numpy()
+    rel = 1e-3 if got.dtype == torch.float32 else 2.0 ** -8
+    err = np.abs(g - ref)
+    tol = rel * np.abs(ref) + 1e-6 * absref + 1e-30
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), "%s: err %.3e tol %.3e at %s (ref %.6e got %.6e)" % (
+        what, err[worst], tol[worst], worst, ref[worst], g[worst])
+
+
+ROW_SHAPES = [(256, 512), (1, 16), (3, 48), (100, 48), (37, 1040), (520, 2048)]
+COL_SHAPES = [(256, 512), (16, 8), (144, 72), (1040, 136), (272, 1024)]
+
+
+# ------------------------------------------------------------------ quantizers
+
+def test_amax():
+    for shape, seed in [((256, 512), 1), ((3, 16), 2), ((1000, 1000), 3), ((4096, 4096), 4)]:
+        bits = wl.student_t_bf16(shape, 3.0, 0.1, seed)
+        ws = tj.alloc_workspace(tj.workspace_bytes(tj.binding.OP_QUANTIZE, shape[0], shape[1], 0))
+        got = float(tj.amax_bf16(dev_bf16(bits), ws).cpu()[0])
+        assert got == float(np.abs(wl.bf16_to_f32(bits)).max())
+
+
+@pytest.mark.parametrize("shape", ROW_SHAPES)
+@pytest.mark.parametrize("rounding,scale_round", [(0, 0), (0, 2), (1, 0), (1, 1)])
+def test_quant_row_tensor_mode(shape, rounding, scale_round):
+    bits = wl.normal_bf16(shape, 1.0, 100 + shape[0], 1e-2, 50.0)
+    ref = oracle.quantize_bf16(bits, 0, rounding, scale_round=scale_round, seed=5, tensor_id=9)
+    got = tj.quantize(dev_bf16(bits), 0, rounding, scale_round=scale_round, seed=5, tensor_id=9)
+    assert_same(got, ref, "row %s r%d s%d" % (shape, rounding, scale_round), check_amax=(rounding == 0))
+
+
+@pytest.mark.parametrize("shape", [(8, 128), (5, 384), (130, 1152)])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_quant_row_block128_mode(shape, rounding):
+    bits = wl.student_t_bf16(shape, 3.0, 0.1, 200 + shape[0])
+    x = bits.copy()
+    x[0, :128] = 0                     # an all-zero outer block
+    ref = oracle.quantize_bf16(x, 0, rounding, outer=oracle.OUTER_BLOCK128, seed=6, tensor_id=1)
+    got = tj.quantize(dev_bf16(x), 0, rounding, outer=tj.binding.OUTER_BLOCK128, seed=6, tensor_id=1)
+    assert_same(got, ref, "row128 %s r%d" % (shape, rounding), check_amax=(rounding == 0))
+
+
+def test_quant_row_amax_supplied_and_edge_values():
+    bits = wl.student_t_bf16((64, 256), 3.0, 0.1, 300)
+    bits[3, 16:32] = 0                 # zero group
+    bits[4, :] = 0x8000                # a row of -0
+    ref = oracle.quantize_bf16(bits, 0, 0)
+    x = dev_bf16(bits)
+    ws = tj.alloc_workspace(4096)
+    amax = tj.amax_bf16(x, ws)
+    got = tj.quantize(x, 0, 0, amax_in=amax)
+    assert_same(got, ref, "amax_in")
+    z = np.zeros((4, 64), dtype=np.uint16)
+    assert_same(tj.quantize(dev_bf16(z), 0, 1, seed=1), oracle.quantize_bf16(z, 0, 1, seed=1), "zeros")
+    tiny = wl.f32_to_bf16(np.full((2, 32), 1e-38, dtype=np.float32))
+    assert_same(tj.quantize(dev_bf16(tiny), 0, 0), oracle.quantize_bf16(tiny, 0, 0), "tiny")
+    huge = wl.f32_to_bf16(np.full((2, 32), 3e38, dtype=np.float32))
+    assert_same(tj.quantize(dev_bf16(huge), 0, 0), oracle.quantize_bf16(huge, 0, 0), "huge")
+
+
+def test_every_bf16_value_up_to_six_as_rounding_argument():
+    """Tensor maximum 2688 and group maximum 6 make S_global = S_block = 1, so the rounding functions
+    see every bf16 value in [-6, 6] exactly (all ties included)."""
+    vals = np.arange(0, 0x40C1, dtype=np.uint16)               # 0 .. 6.0
+    vals = np.concatenate([vals, vals | 0x8000])
+    pad = (-len(vals)) % 15
+    vals = np.concatenate([vals, np.zeros(pad, dtype=np.uint16)])
+    blocks = vals.reshape(-1, 15)
+    six = np.full((blocks.shape[0], 1), 0x40C0, dtype=np.uint16)
+    body = np.concatenate([blocks, six], axis=1).reshape(-1)
+    lead = np.zeros(16, dtype=np.uint16)
+    lead[0] = wl.f32_to_bf16(np.array([2688.0], dtype=np.float32))[0]
+    flat = np.concatenate([lead, body])
+    pad = (-len(flat)) % 64
+    flat = np.concatenate([flat, np.zeros(pad, dtype=np.uint16)])
+    bits = flat.reshape(-1, 64)
+    for rounding, sr in [(0, 1), (0, 2), (1, 2), (1, 1)]:
+        for seed in (0, 1):
+            ref = oracle.quantize_bf16(bits, 0, rounding, scale_round=sr, seed=seed, tensor_id=2)
+            assert ref.gscale[0] == 1.0 and ref.scales[0, 1] == 0x38
+            got = tj.quantize(dev_bf16(bits), 0, rounding, scale_round=sr, seed=seed, tensor_id=2)
+            assert_same(got, ref, "all-bf16 r%d" % rounding)
+
+
+def test_every_scale_code_is_reachable_and_exact():
+    """Group maxima 6 * v for every E4M3 value v (tensor maximum 2688): the scale byte must be v's code."""
+    L = oracle.lib()
+    codes = np.arange(1, 0x7F)
+    v = np.array([L.oracle_e4m3_value(int(c)) for c in codes], dtype=np.float32)
+    x = np.zeros((len(codes), 16), dtype=np.float32)
+    x[:, 3] = 6.0 * v
+    x[:, 7] = -2.0 * v
+    x[-1, 3] = 2688.0
+    bits = wl.f32_to_bf16(x)
+    assert np.array_equal(wl.bf16_to_f32(bits), x)
+    for rounding in (0, 1):
+        ref = oracle.quantize_bf16(bits, 0, rounding, seed=3)
+        assert np.array_equal(ref.scales[:, 0], codes.astype(np.uint8))
+        got = tj.quantize(dev_bf16(bits), 0, rounding, seed=3)
+        assert_same(got, ref, "scale codes")
+
+
+@pytest.mark.parametrize("shape", COL_SHAPES)
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_quant_col(shape, rounding):
+    bits = wl.normal_bf16(shape, 1e-3, 400 + shape[0], 1e-2, 30.0)
+    ref = oracle.quantize_bf16(bits, 1, rounding, seed=8, tensor_id=5)
+    got = tj.quantize(dev_bf16(bits), 1, rounding, seed=8, tensor_id=5)
+    assert_same(got, ref, "col %s r%d" % (shape, rounding))
+
+
+@pytest.mark.parametrize("shape", [(256, 512), (16, 16), (144, 80), (1040, 144), (272, 1024)])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_requant_col(shape, rounding):
+    bits = wl.normal_bf16(shape, 0.02, 500 + shape[0], 1e-2, 30.0)
+    src_ref = oracle.quantize_bf16(bits, 0, 0)
+    ref = oracle.requantize(src_ref, 1, rounding, seed=4, tensor_id=6)
+    src_gpu = tj.quantize(dev_bf16(bits), 0, 0)
+    assert_same(src_gpu, src_ref, "requant source", check_amax=True)
+    got = tj.quantize(src_gpu, 1, rounding, seed=4, tensor_id=6)
+    assert_same(got, ref, "requant %s r%d" % (shape, rounding))
+
+
+# ------------------------------------------------------------------------ GEMM
+
+GEMM_SHAPES = [(128, 128, 64), (32, 32, 64), (200, 72, 192), (256, 384, 512), (130, 258, 1024), (64, 96, 4096),
+               (16, 16, 8192)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("out_dtype", [1, 0])
+def test_gemm_nt(M, N, K, out_dtype):
+    A = oracle.quantize_bf16(wl.normal_bf16((M, K), 1.0, 600 + M, 1e-2, 50.0), 0, 0)
+    B = oracle.quantize_bf16(wl.normal_bf16((N, K), 0.02, 601 + N), 0, 1, seed=2)
+    ref, absref = oracle.gemm_nt(A, B)
+    got = tj.gemm_nt(to_dev(A), to_dev(B), out_dtype)
+    torch.cuda.synchronize()
+    check_product(got, ref, absref, "gemm %dx%dx%d" % (M, N, K))
+
+
+def test_gemm_exact_on_integer_operands():
+    """Scales 1 and grid-valued operands: the product is a small-integer matrix product, exact in FP32."""
+    rng = np.random.default_rng(7)
+    grid = oracle.FP4_VALUES
+    M, N, K = 96, 160, 256
+
+    def operand(rows, big_col, zero_col):
+        m = rng.integers(0, 8, (rows, K))
+        m[:, ::16] = 7                                      # a 6 in every group -> S_block = 1
+        sg = rng.integers(0, 2, (rows, K))
+        x = np.where(sg == 1, -grid[m], grid[m]).astype(np.float32)
+        x[:, zero_col] = 0.0                                # the other operand's 2688 meets only zeros
+        x[0, big_col] = 2688.0                              # S_global = 1
+        return wl.f32_to_bf16(x)
+
+    A = oracle.quantize_bf16(operand(M, 1, 2), 0, 0)
+    B = oracle.quantize_bf16(operand(N, 2, 1), 0, 0)
+    assert A.gscale[0] == 1.0 and B.gscale[0] == 1.0
+    ref, _ = oracle.gemm_nt(A, B)
+    got = tj.gemm_nt(to_dev(A), to_dev(B), 1).double().cpu().numpy()
+    assert np.array_equal(got, ref)
+
+
+def test_gemm_all_scale_codes_and_all_element_codes():
+    """Every E4M3 scale byte (subnormal ones included) times every E2M1 code expands exactly."""
+    M, N, K = 128, 32, 64
+    codes = np.zeros((M, K // 2), dtype=np.uint8)
+    scales = np.zeros((M, K // 16), dtype=np.uint8)
+    for r in range(M):
+        scales[r, :] = [(r * 4 + j) % 0x7F for j in range(4)]
+        nib = (np.arange(K) + r) % 16
+        codes[r] = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
+    A = oracle.NVFP4(codes, scales, np.array([1.0], np.float32), 0.0, M, K, 0)
+    bc = np.zeros((N, K // 2), dtype=np.uint8)
+    for r in range(N):
+        bc[r, (r % 32)] = 0x02 if r % 2 == 0 else 0x20        # a single 1.0 per row: picks one column of A
+    B = oracle.NVFP4(bc, np.full((N, K // 16), 0x38, np.uint8), np.array([1.0], np.float32), 0.0, N, K, 0)
+    ref, _ = oracle.gemm_nt(A, B)
+    got = tj.gemm_nt(to_dev(A), to_dev(B), 1).double().cpu().numpy()
+    assert np.array_equal(got, ref)
+
+
+# ---------------------------------------------------------------- linear layer
+
+def run_linear_case(N, D, C, seed, kind="block", sr_seed=0, layer_id=1, out_dtype=1, sample=None):
+    Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed, kind)
+    X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
+    Y, Xq, Wq = tj.linear_fwd(X, W, out_dtype)
+    dX = tj.linear_bwd_dx(dY, Wq, sr_seed, layer_id, out_dtype)
+    dW = tj.linear_bwd_dw(dY, Xq, sr_seed, layer_id, out_dtype)
+    torch.cuda.synchronize()
+    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    assert_same(Xq, oXq, "Q1(X)", check_amax=True)
+    assert_same(Wq, oWq, "Q2(W)", check_amax=True)
+    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, sr_seed, layer_id)
+    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, sr_seed, layer_id)
+    rng = np.random.default_rng(seed)
+
+    def rows_of(n):
+        if sample is None or n <= sample:
+            return None
+        return np.sort(rng.choice(n, sample, replace=False))
+
+    for name, got, qa, qb in (("Y", Y, oXq, oWq), ("dX", dX, o3, o4), ("dW", dW, o5, o6)):
+        ra = rows_of(qa.rows)
+        ref, absref = oracle.gemm_nt(qa, qb, rows_a=ra)
+        g = got if ra is None else got[torch.from_numpy(ra).cuda()]
+        check_product(g, ref, absref, "%s %dx%dx%d" % (name, N, D, C))
+    return Xq, Wq
+
+
+def test_linear_config1_full():
+    """Single layer 256 x 512 -> 512, RTN forward, SR backward, seed 0: checked in full, both output types."""
+    run_linear_case(256, 512, 512, seed=0, sr_seed=0, out_dtype=1)
+    run_linear_case(256, 512, 512, seed=0, sr_seed=0, out_dtype=0)
+
+
+def test_linear_ragged_shapes():
+    run_linear_case(192, 320, 448, seed=5, sr_seed=3)
+    run_linear_case(64, 64, 64, seed=6, sr_seed=4)
+    run_linear_case(1088, 192, 576, seed=7, sr_seed=5, sample=128)
+
+
+def test_backward_operands_match_oracle_bitwise():
+    """The temporaries of the backward calls (Q3..Q6) are produced by the same kernels nvfp4_quantize exposes."""
+    Xb, Wb, dYb = wl.linear_inputs(256, 384, 512, seed=9)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, 13, 7)
+    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, 13, 7)
+    dY = dev_bf16(dYb)
+    Xq = tj.quantize(dev_bf16(Xb), 0, 0)
+    Wq = tj.quantize(dev_bf16(Wb), 0, 0)
+    assert_same(tj.quantize(dY, 0, 1, seed=13, tensor_id=7 * 8 + 3), o3, "Q3")
+    assert_same(tj.quantize(Wq, 1, 1, seed=13, tensor_id=7 * 8 + 4), o4, "Q4")
+    assert_same(tj.quantize(dY, 1, 1, seed=13, tensor_id=7 * 8 + 5), o5, "Q5")
+    assert_same(tj.quantize(Xq, 1, 1, seed=13, tensor_id=7 * 8 + 6), o6, "Q6")
+
+
+def test_same_seed_same_bytes_other_seed_other_bytes():
+    bits = wl.normal_bf16((512, 1024), 1e-3, 11)
+    x = dev_bf16(bits)
+    a = tj.quantize(x, 1, 1, seed=1, tensor_id=2)
+    b = tj.quantize(x, 1, 1, seed=1, tensor_id=2)
+    c = tj.quantize(x, 1, 1, seed=2, tensor_id=2)
+    torch.cuda.synchronize()
+    assert torch.equal(a.codes, b.codes) and torch.equal(a.scales, b.scales)
+    assert (a.codes != c.codes).float().mean().item() > 0.2

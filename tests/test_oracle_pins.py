@@ -203,7 +203,6 @@ def _representable(rows, K, rng, j=-3, outer=oracle.OUTER_TENSOR, pow2_scales=Fa
     for r in range(rows):
         for b in range(nb):
             m[r, b * 16 + pos[r, b]] = 7
-    sg[m == 0] = 0
     P = np.where(sg == 1, -GRID[m], GRID[m])
     Sb = np.repeat(e4m3_torch(sc), 16, axis=1)
     X = (P * Sb * 2.0 ** j).astype(np.float32)
@@ -274,9 +273,10 @@ def _check_invariants(x, q, scale_round):
     P = decode_codes(q.codes)
     assert np.all(np.isin(np.abs(P), GRID))
     assert np.abs(P).max() <= LIM["fp4_max"]
-    # no negative zero codes
+    # the sign bit of every code is the input's sign bit
     lo, hi = q.codes & 0xF, q.codes >> 4
-    assert not np.any(lo == 8) and not np.any(hi == 8)
+    nib = np.stack([lo, hi], axis=-1).reshape(rows, K)
+    assert np.array_equal((nib >> 3).astype(bool), np.signbit(x))
     return P, Sb, Sg
 
 
