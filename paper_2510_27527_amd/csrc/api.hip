@@ -149,16 +149,18 @@ int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nv
     if (pl.out_rows == 0 || pl.out_K == 0) return NVFP4_OK;
     hipError_t e;
     if (pl.src_kind == NVFP4_SRC_BF16) {
+        if (pl.rounding != NVFP4_ROUND_RTN) o.amax_deq = nullptr;   // only forward operands are re-quantized
+        bool zeroed = o.amax_deq == nullptr;
         if (pl.outer == NVFP4_OUTER_TENSOR) {
             if (cfg->amax_in) {
                 p.amax_scalar = cfg->amax_in;
             } else {
-                p.npart = launch_amax_partials(src, pl.R * pl.C, partials, st);
+                p.npart = launch_amax_partials(src, pl.R * pl.C, partials, o.amax_deq, st);
                 p.amax_partials = partials;
+                zeroed = true;
             }
         }
-        if (o.amax_deq && pl.rounding == NVFP4_ROUND_RTN) launch_zero_scalar(o.amax_deq, st);
-        if (pl.rounding != NVFP4_ROUND_RTN) o.amax_deq = nullptr;
+        if (!zeroed) launch_zero_scalar(o.amax_deq, st);
         e = pl.axis == 0 ? launch_quant_row_bf16(src, pl.R, pl.C, p, o, st)
                          : launch_quant_col_bf16(src, pl.R, pl.C, p, o, st);
     } else {
@@ -251,7 +253,7 @@ int nvfp4_amax_bf16(const void *src, int64_t n, float *amax_out, void *ws, size_
     if (!aligned16(src)) return NVFP4_ERR_ALIGN;
     if (!ws || ws_bytes < partials_bytes()) return NVFP4_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int npart = launch_amax_partials(src, n, static_cast<float *>(ws), st);
+    const int npart = launch_amax_partials(src, n, static_cast<float *>(ws), nullptr, st);
     launch_amax_final(static_cast<float *>(ws), npart, amax_out, st);
     return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }

@@ -34,8 +34,9 @@ struct PackedSrc {
     int outer;
 };
 
-// partial maxima of |x| over a bf16 array of n elements (n % 8 == 0); returns the number of partials written
-int launch_amax_partials(const void *src, int64_t n, float *partials, hipStream_t st);
+// partial maxima of |x| over a bf16 array of n elements (n % 8 == 0); returns the number of partials written;
+// zero_me (optional) is a device float the kernel also clears
+int launch_amax_partials(const void *src, int64_t n, float *partials, float *zero_me, hipStream_t st);
 // reduce partials to one scalar
 void launch_amax_final(const float *partials, int npart, float *out, hipStream_t st);
 // zero one float
@@ -49,9 +50,6 @@ hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const Qu
                                  hipStream_t st);
 // column-wise re-quantization of an NVFP4 [R x C] tensor: output [C x R] grouped along R
 hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
-                              hipStream_t st);
-// row-wise re-quantization of an NVFP4 [R x C] tensor (same grouping axis)
-hipError_t launch_requant_row(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
                               hipStream_t st);
 
 struct GemmOperand {

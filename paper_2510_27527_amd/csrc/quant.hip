@@ -71,19 +71,28 @@ __device__ __forceinline__ uint32_t quant8(const float (&x)[8], float r, uint32_
     return out;
 }
 
-__device__ __forceinline__ void publish_deq_max(float v, float *dst)
+// workgroup maximum -> one atomic, and only if it can still raise the published value (the
+// published value only grows, so a stale read costs an extra atomic, never a wrong result)
+__device__ __forceinline__ void publish_deq_max(float v, float *dst, float *red)
 {
     v = wave_max(v);
-    if ((threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<unsigned int *>(dst), f2u(v));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        v = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (v > __builtin_nontemporal_load(dst)) atomicMax(reinterpret_cast<unsigned int *>(dst), f2u(v));
+    }
 }
 
 // ------------------------------------------------------------------------------- amax ----
 
 __global__ __launch_bounds__(kThreads) void amax_partials_kernel(const uint4 *__restrict__ src, int64_t nchunks,
-                                                                 float *__restrict__ partials)
+                                                                 float *__restrict__ partials, float *zero_me)
 {
     __shared__ float red[4];
-    ushort2_t m = {0, 0};
+    if (zero_me && blockIdx.x == 0 && threadIdx.x == 0) zero_me[0] = 0.0f;
+    uint32_t m = 0;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     for (; c + 3 * stride < nchunks; c += 4 * stride) {
@@ -91,13 +100,13 @@ __global__ __launch_bounds__(kThreads) void amax_partials_kernel(const uint4 *__
         uint32_t a = absmax8_bits(v0), b = absmax8_bits(v1), d = absmax8_bits(v2), e = absmax8_bits(v3);
         uint32_t ab = a > b ? a : b, de = d > e ? d : e;
         uint32_t q = ab > de ? ab : de;
-        m.x = m.x > q ? m.x : (unsigned short)q;
+        m = m > q ? m : q;
     }
     for (; c < nchunks; c += stride) {
         uint32_t q = absmax8_bits(src[c]);
-        m.x = m.x > q ? m.x : (unsigned short)q;
+        m = m > q ? m : q;
     }
-    float f = wave_max(u2f((uint32_t)m.x << 16));
+    float f = wave_max(u2f(m << 16));
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = f;
     __syncthreads();
     if (threadIdx.x == 0) partials[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
@@ -127,9 +136,18 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
     const int tid = threadIdx.x;
     fill_inv_table(inv_tab);
     OuterScale os;
+    // Largest dequantized magnitude.  In tensor mode the group holding the tensor maximum always gets
+    // the scale 448 and its largest element the code 6, so the maximum is 6 * 448 * S_g in closed form;
+    // only a floored S_g (maximum below 2688 * 2^-100) needs the reduction over all groups.
+    bool reduce_deq = DEQ && OUTER == 1;
     if (OUTER == 0) {
-        os = outer_scale(block_tensor_amax(a, red));
+        const float amax = block_tensor_amax(a, red);
+        os = outer_scale(amax);
         if (blockIdx.x == 0 && tid == 0) a.gscale[0] = os.S_g;
+        if (DEQ) {
+            reduce_deq = os.S_g == 0x1p-100f;
+            if (!reduce_deq && blockIdx.x == 0 && tid == 0) a.amax_deq[0] = amax == 0.0f ? 0.0f : 2688.0f * os.S_g;
+        }
     }
     __syncthreads();
     float deq = 0.0f;
@@ -169,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
                     if (c + 2 * b < nchunks) a.scales[(c >> 1) + b] = (uint8_t)(s4 >> (8 * b));
             }
         }
-        if (DEQ) {
+        if (DEQ && reduce_deq) {
             // the group's largest element gets the group's largest code (rounding is monotone)
             const uint32_t mm = e2m1_rtn(amax_b * r) & 7u;
             float val = e2m1_value(mm) * e4m3_value(sc);
@@ -177,9 +195,9 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
             deq = fmaxf(deq, val);
         }
     }
-    if (DEQ) {
+    if (DEQ && reduce_deq) {
         if (OUTER == 0) deq = deq * os.S_g;
-        publish_deq_max(deq, a.amax_deq);
+        publish_deq_max(deq, a.amax_deq, red);
     }
 }
 
@@ -338,13 +356,13 @@ void launch_col_t(const ColArgs &a, int rounding, int scale_up, hipStream_t st)
 
 }  // namespace
 
-int launch_amax_partials(const void *src, int64_t n, float *partials, hipStream_t st)
+int launch_amax_partials(const void *src, int64_t n, float *partials, float *zero_me, hipStream_t st)
 {
     const int64_t nchunks = n / 8;
     int64_t want = (nchunks + (int64_t)kThreads * 8 - 1) / ((int64_t)kThreads * 8);
     int grid = (int)(want < 1 ? 1 : (want > kMaxAmaxPartials ? kMaxAmaxPartials : want));
     hipLaunchKernelGGL(amax_partials_kernel, dim3(grid), dim3(kThreads), 0, st,
-                       reinterpret_cast<const uint4 *>(src), nchunks, partials);
+                       reinterpret_cast<const uint4 *>(src), nchunks, partials, zero_me);
     return grid;
 }
 
