@@ -74,7 +74,7 @@ int check_gemm_operand(const nvfp4_tensor *t)
     if (t->outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;
     rc = check_shape(t->rows, t->K, t->outer_mode);
     if (rc) return rc;
-    if (t->K % 64 != 0) return NVFP4_ERR_SHAPE;
+    if (t->K % 64 != 0 || t->K > ((int64_t)1 << 22)) return NVFP4_ERR_SHAPE;   // 32-bit tile offsets in the kernel
     return NVFP4_OK;
 }
 

@@ -60,31 +60,65 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
 
+// Global -> LDS copies that bypass registers: every lane supplies a global address, the wave's data
+// lands at lds_addr + lane * 16 (or * 4).  Written as inline assembly so that completion is tracked only
+// by the explicit s_waitcnt vmcnt(n) of the pipeline (the compiler would otherwise wait for every
+// outstanding copy before each LDS read).  lds_addr must be wave-uniform.
+// The global address is a wave-uniform 64-bit base plus a 32-bit unsigned byte offset per lane.
+__device__ __forceinline__ void lds_dma16(const void *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
+}
+__device__ __forceinline__ void lds_dma4(const void *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
+}
+
 __device__ __forceinline__ uint32_t pick(uint4 v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
 // Tile TM*64 x TN*64 per workgroup (2 x 2 waves, TM x TN MFMA tiles of 32 x 32 each), NC chunks of
-// 64 k per pipeline stage, two stages in LDS.  Codes go global -> LDS directly (128 bits per lane, a
-// wave fills 1 KB = 64 consecutive 16-byte slots); scale bytes pass through registers.
-// LDS slot of (row, 16-byte piece p of the stage's row segment) = row * SLOTS + (p ^ f(row)).
+// 64 k per pipeline stage, three stage buffers in LDS.  Codes and scale bytes go global -> LDS
+// directly (a wave instruction fills 64 consecutive 16-byte / 4-byte slots), two stages ahead.
+//   codes : slot of (row, 16-byte piece p of the stage's row segment) = row * SLOTS + (p ^ swz(row))
+//   scales: dword of (chunk c, row) = c * ROWS + row   (A rows first, then B rows)
+// The reduction is a software pipeline over 16-wide k steps: while the MFMAs of step g run, the
+// FP4 -> FP16 expansion of step g + 1 is issued (about four VALU instructions per MFMA), and the
+// raw codes of the next chunk are fetched from LDS one step earlier.  One barrier per stage, placed
+// two steps before its end so that the first step of the next stage is expanded under the last
+// MFMAs of this one.  Rows past M / N read clamped (valid) addresses and are never stored; chunks
+// past the end of K get zero scales.
+template <int TM, int TN>
+struct RawFrags {
+    uint4 qa[TM], qb[TN];       // 32 codes per fragment
+    uint32_t sa[TM], sb[TN];    // the chunk's four scale bytes per fragment row
+    uint32_t live;              // 0xFF, or 0 for a chunk past the end of K (its scales count as zero)
+};
+template <int TM, int TN>
+struct OpFrags {
+    half8_t a[TM], b[TN];
+};
+
 template <int TM, int TN, int NC, int OUT>   // OUT: 0 bf16, 1 f32, 2 raw f32 split-K partial
-__global__ __launch_bounds__(kThreads, (TM * TN >= 16 ? 1 : 2)) void gemm_nt_kernel(GemmArgs g)
+__global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kernel(GemmArgs g)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 64 * TM, BN = 64 * TN, ROWS = BM + BN;
     constexpr int SLOTS = 2 * NC;                       // 16-byte pieces per row per stage
     constexpr int A_SLOTS = BM * SLOTS, B_SLOTS = BN * SLOTS;
-    constexpr int LA = A_SLOTS / kThreads, LB = B_SLOTS / kThreads;
-    constexpr int STAGE_U4 = A_SLOTS + B_SLOTS;          // uint4 per stage (codes)
-    constexpr int STAGE_SC = (BM + BN) * NC;             // dwords per stage (scales)
-    static_assert(BM <= kThreads && BN <= kThreads, "one scale row per thread");
-    static_assert(LA >= 1 && LB >= 1, "tile too small");
+    constexpr int LA = A_SLOTS / kThreads, LB = B_SLOTS / kThreads, LS = ROWS * NC / kThreads;
+    constexpr int NLOAD = LA + LB + LS;                  // direct-to-LDS loads per thread per stage
+    constexpr int CODE_BYTES = (A_SLOTS + B_SLOTS) * 16;
+    constexpr int STAGE_BYTES = CODE_BYTES + ROWS * NC * 4;
+    constexpr int STEPS = NC * 4;
+    static_assert(NC % 2 == 0, "chunk parity must repeat per stage");
+    static_assert(LA >= 1 && LB >= 1 && LS >= 1 && (ROWS * NC) % kThreads == 0, "tile too small");
+    static_assert(NLOAD <= 15, "vmcnt immediate below assumes at most 15 loads per stage");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    uint4 *codes_lds = reinterpret_cast<uint4 *>(smem_raw);                            // [2][STAGE_U4]
-    uint32_t *scales_lds = reinterpret_cast<uint32_t *>(smem_raw + 2 * STAGE_U4 * 16); // [2][STAGE_SC]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int lr = lane & 31, kg = lane >> 5;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)smem_raw;
 
     // workgroup -> tile: consecutive ids of one XCD (ids are dealt round-robin over 8 XCDs) walk
     // down a column of tiles, in groups of 8 tile rows
@@ -111,69 +145,6 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 16 ? 1 : 2)) void gemm_nt_ker
     const int nk = (nchunks + NC - 1) / NC;
     const int64_t cstride = g.K / 2, sstride = g.K / 16;
 
-    // per-thread constants of the code loads: global row pointer and piece index of each slot
-    const uint8_t *arow[LA];
-    int apiece[LA];
-#pragma unroll
-    for (int u = 0; u < LA; ++u) {
-        const int slot = (u * 4 + wave) * 64 + lane, row = slot / SLOTS, pos = slot % SLOTS;
-        int64_t gr = m0 + row;
-        if (gr >= g.M) gr = g.M - 1;
-        arow[u] = g.a_codes + gr * cstride;
-        apiece[u] = pos ^ ((row >> 1) & (SLOTS - 1));
-    }
-    const uint8_t *brow[LB];
-    int bpiece[LB];
-#pragma unroll
-    for (int u = 0; u < LB; ++u) {
-        const int slot = (u * 4 + wave) * 64 + lane, row = slot / SLOTS, pos = slot % SLOTS;
-        int64_t gr = n0 + row;
-        if (gr >= g.N) gr = g.N - 1;
-        brow[u] = g.b_codes + gr * cstride;
-        bpiece[u] = pos ^ ((row >> 1) & (SLOTS - 1));
-    }
-    const bool a_row_ok = tid < BM && m0 + tid < g.M;
-    const bool b_row_ok = tid < BN && n0 + tid < g.N;
-    const uint8_t *a_srow = g.a_scales + (a_row_ok ? (m0 + tid) : 0) * sstride;
-    const uint8_t *b_srow = g.b_scales + (b_row_ok ? (n0 + tid) : 0) * sstride;
-
-    uint32_t sa[NC], sb[NC];
-
-    auto issue_loads = [&](int kt, int buf) {
-        const int64_t c0 = cbeg + (int64_t)kt * NC;           // first chunk of the stage
-        uint4 *dst = codes_lds + buf * STAGE_U4;
-#pragma unroll
-        for (int u = 0; u < LA; ++u) {
-            int64_t half_chunk = c0 * 2 + apiece[u];          // units of 32 k = 16 bytes
-            if (half_chunk >= cend * 2) half_chunk = cend * 2 - 1;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(arow[u] + half_chunk * 16),
-                (__attribute__((address_space(3))) void *)(dst + (u * 4 + wave) * 64), 16, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < LB; ++u) {
-            int64_t half_chunk = c0 * 2 + bpiece[u];
-            if (half_chunk >= cend * 2) half_chunk = cend * 2 - 1;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(brow[u] + half_chunk * 16),
-                (__attribute__((address_space(3))) void *)(dst + A_SLOTS + (u * 4 + wave) * 64), 16, 0, 0);
-        }
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const bool in = c0 + c < cend;
-            sa[c] = (a_row_ok && in) ? *reinterpret_cast<const uint32_t *>(a_srow + (c0 + c) * 4) : 0u;
-            sb[c] = (b_row_ok && in) ? *reinterpret_cast<const uint32_t *>(b_srow + (c0 + c) * 4) : 0u;
-        }
-    };
-    auto write_scales = [&](int buf) {
-        uint32_t *dst = scales_lds + buf * STAGE_SC;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            if (tid < BM) dst[tid * NC + c] = sa[c];
-            if (tid < BN) dst[BM * NC + tid * NC + c] = sb[c];
-        }
-    };
-
     float16_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -182,58 +153,150 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 16 ? 1 : 2)) void gemm_nt_ker
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    if (nk > 0) {
-        issue_loads(0, 0);
-        write_scales(0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) issue_loads(kt + 1, buf ^ 1);
-        const uint4 *ac = codes_lds + buf * STAGE_U4;
-        const uint4 *bc = ac + A_SLOTS;
-        const uint32_t *as = scales_lds + buf * STAGE_SC;
-        const uint32_t *bs = as + BM * NC;
+    if (nchunks > 0) {
+        // Per-lane constants of the loads: 32-bit byte offsets from the tile's (uniform) base pointers, the
+        // piece / chunk index each load covers, and a bit mask of the loads whose row exists.
+        uint32_t coff[LA + LB], soff[LS];
+        uint32_t cpieces = 0, schunks = 0, rowmask = 0;      // 4 bits per load / 1 bit per load
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            // this lane's 32 codes (k = 32 kg .. 32 kg + 31 of the chunk) and 2 scale bytes per fragment
-            uint4 qa[TM], qb[TN];
-            half2_t fa[TM][2], fb[TN][2];
+        for (int u = 0; u < LA + LB; ++u) {
+            const bool isA = u < LA;
+            const int slot = ((isA ? u : u - LA) * 4 + wave) * 64 + lane, row = slot / SLOTS, pos = slot % SLOTS;
+            const int piece = pos ^ ((row >> 1) & (SLOTS - 1));
+            coff[u] = (uint32_t)row * (uint32_t)cstride + (uint32_t)piece * 16u;
+            cpieces |= (uint32_t)piece << (4 * u);
+            if ((isA ? m0 : n0) + row < (isA ? g.M : g.N)) rowmask |= 1u << u;
+        }
+#pragma unroll
+        for (int u = 0; u < LS; ++u) {
+            const int q = u * 4 + wave, c = q / (ROWS / 64), row = (q % (ROWS / 64)) * 64 + lane;
+            const bool isA = row < BM;
+            soff[u] = (uint32_t)(isA ? row : row - BM) * (uint32_t)sstride + (uint32_t)c * 4u;
+            schunks |= (uint32_t)c << (4 * u);
+            if ((isA ? m0 + row : n0 + row - BM) < (isA ? g.M : g.N)) rowmask |= 1u << (LA + LB + u);
+        }
+        const bool tile_full = m0 + BM <= g.M && n0 + BN <= g.N;
+        const uint8_t *a_cbase = g.a_codes + m0 * cstride + cbeg * 32, *b_cbase = g.b_codes + n0 * cstride + cbeg * 32;
+        const uint8_t *a_sbase = g.a_scales + m0 * sstride + cbeg * 4, *b_sbase = g.b_scales + n0 * sstride + cbeg * 4;
+
+        // All loads of stage kt.  Interior tiles and stages fully inside the split take the straight path;
+        // otherwise loads of missing rows or of chunks past the end are skipped (their LDS slots keep stale
+        // bytes: missing rows are never stored, late chunks get zero scales when they are read).
+        auto issue_loads = [&](int kt, int buf) {
+            const int64_t c0 = (int64_t)kt * NC;                  // first chunk of the stage, relative to cbeg
+            const uint32_t dst = lds_base + buf * STAGE_BYTES;
+            const uint8_t *ac = a_cbase + c0 * 32, *bc = b_cbase + c0 * 32;
+            const uint8_t *as = a_sbase + c0 * 4, *bs = b_sbase + c0 * 4;
+            if (tile_full && c0 + NC <= nchunks) {
+#pragma unroll
+                for (int u = 0; u < LA + LB; ++u) {
+                    const int lds_slot = (u < LA ? 0 : A_SLOTS) + ((u < LA ? u : u - LA) * 4 + wave) * 64;
+                    lds_dma16(u < LA ? ac : bc, coff[u], dst + lds_slot * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < LS; ++u) {
+                    const int q = u * 4 + wave;
+                    lds_dma4((q % (ROWS / 64)) * 64 < BM ? as : bs, soff[u], dst + CODE_BYTES + q * 256);
+                }
+            } else {
+                // Same number of instructions (the pipeline counts them with vmcnt); loads that have nothing
+                // to fetch are pointed at the first bytes of the tile instead.
+                const bool stage_ok = c0 < nchunks;
+#pragma unroll
+                for (int u = 0; u < LA + LB; ++u) {
+                    const int lds_slot = (u < LA ? 0 : A_SLOTS) + ((u < LA ? u : u - LA) * 4 + wave) * 64;
+                    const int64_t piece = c0 * 2 + ((cpieces >> (4 * u)) & 15);
+                    const bool ok = ((rowmask >> u) & 1u) && piece < (int64_t)nchunks * 2;
+                    lds_dma16(stage_ok ? (u < LA ? ac : bc) : (u < LA ? a_cbase : b_cbase), ok ? coff[u] : 0u,
+                              dst + lds_slot * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < LS; ++u) {
+                    const int q = u * 4 + wave;
+                    const bool isA = (q % (ROWS / 64)) * 64 < BM;
+                    const int64_t c = c0 + ((schunks >> (4 * u)) & 15);
+                    const bool ok = ((rowmask >> (LA + LB + u)) & 1u) && c < nchunks;
+                    lds_dma4(stage_ok ? (isA ? as : bs) : (isA ? a_sbase : b_sbase), ok ? soff[u] : 0u,
+                             dst + CODE_BYTES + q * 256);
+                }
+            }
+        };
+
+        auto read_raw = [&](RawFrags<TM, TN> &r, int buf, int c, bool live) {
+            const uint4 *codes = reinterpret_cast<const uint4 *>(smem_raw + buf * STAGE_BYTES);
+            const uint32_t *scales = reinterpret_cast<const uint32_t *>(smem_raw + buf * STAGE_BYTES + CODE_BYTES) + c * ROWS;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = (wm * TM + i) * 32 + lr;
-                qa[i] = ac[row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
-                const uint32_t s = as[row * NC + c] >> (16 * kg);
-                fa[i][0] = scale_pair(s & 0xFFu);
-                fa[i][1] = scale_pair((s >> 8) & 0xFFu);
+                r.qa[i] = codes[row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
+                r.sa[i] = scales[row];
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int row = (wn * TN + j) * 32 + lr;
-                qb[j] = bc[row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
-                const uint32_t s = bs[row * NC + c] >> (16 * kg);
-                fb[j][0] = scale_pair(s & 0xFFu);
-                fb[j][1] = scale_pair((s >> 8) & 0xFFu);
+                r.qb[j] = codes[A_SLOTS + row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
+                r.sb[j] = scales[BM + row];
+            }
+            r.live = live ? 0xFFu : 0u;
+        };
+
+        half2_t fA[TM], fB[TN];
+        auto expand = [&](OpFrags<TM, TN> &o, const RawFrags<TM, TN> &r, int ks) {
+            if ((ks & 1) == 0) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fA[i] = scale_pair((r.sa[i] >> (16 * kg + 4 * ks)) & r.live);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fB[j] = scale_pair((r.sb[j] >> (16 * kg + 4 * ks)) & r.live);
             }
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                half8_t av[TM], bv[TN];
+            for (int i = 0; i < TM; ++i) o.a[i] = expand8(pick(r.qa[i], ks), fA[i]);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) av[i] = expand8(pick(qa[i], ks), fa[i][ks >> 1]);
+            for (int j = 0; j < TN; ++j) o.b[j] = expand8(pick(r.qb[j], ks), fB[j]);
+        };
+
+        RawFrags<TM, TN> raw[2];
+        OpFrags<TM, TN> op[2];
+
+        issue_loads(0, 0);
+        issue_loads(1, 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | NLOAD);       // vmcnt(NLOAD): stage 0 has landed
+        __syncthreads();
+        read_raw(raw[0], 0, 0, true);
+        expand(op[0], raw[0], 0);
+
+        int buf = 0;
+        for (int kt = 0; kt < nk; ++kt) {
+            const int nbuf = buf == 2 ? 0 : buf + 1;
+            issue_loads(kt + 2, nbuf == 2 ? 0 : nbuf + 1);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bv[j] = expand8(pick(qb[j], ks), fb[j][ks >> 1]);
+            for (int gs = 0; gs < STEPS; ++gs) {
+                const int c = gs / 4, ks = gs % 4;
+                if (ks == 1 && c + 1 < NC) read_raw(raw[(c + 1) & 1], buf, c + 1, kt * NC + c + 1 < nchunks);
+                if (gs == STEPS - 2) {
+                    __builtin_amdgcn_s_waitcnt(0x0F70 | NLOAD);   // all but the newest stage's loads: stage kt+1 has landed
+                    __syncthreads();
+                    read_raw(raw[0], nbuf, 0, (kt + 1) * NC < nchunks);
+                }
+                if (gs + 1 < STEPS) expand(op[(gs + 1) & 1], raw[((gs + 1) / 4) & 1], (gs + 1) % 4);
+                else expand(op[0], raw[0], 0);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[i], bv[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].a[i], op[gs & 1].b[j], acc[i][j], 0, 0, 0);
+                // issue order: one MFMA, then (in the steps that fetch raw fragments) two LDS reads, then its
+                // share of the expansion's VALU instructions
+                const bool fetch = (ks == 1 && c + 1 < NC) || gs == STEPS - 2;
+#pragma unroll
+                for (int q = 0; q < TM * TN; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (fetch && q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, (8 * (TM + TN) + TM * TN - 1) / (TM * TN) + 1, 0);
+                }
             }
+            buf = nbuf;
         }
-        if (kt + 1 < nk) write_scales(buf ^ 1);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
+        __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the look-ahead loads before the LDS is released
     }
 
     // epilogue: acc element e of lane: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
@@ -257,7 +320,6 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 16 ? 1 : 2)) void gemm_nt_ker
                     else outh[m * g.N + n] = (uint16_t)f32_to_bf16_bits(v);
                 }
             }
-            asm volatile("" ::: "memory");       // one tile at a time: keeps the accumulator copies out of VGPRs
         }
 }
 
@@ -333,7 +395,7 @@ template <int TM, int TN, int OUT>
 hipError_t launch_cfg(const GemmArgs &g, dim3 grid, hipStream_t st)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int lds = 2 * ((BM + BN) * 2 * kNC * 16 + (BM + BN) * kNC * 4);
+    constexpr int lds = 3 * ((BM + BN) * 2 * kNC * 16 + (BM + BN) * kNC * 4);
     auto kern = gemm_nt_kernel<TM, TN, kNC, OUT>;
     static bool attr_set = false;
     if (!attr_set) {
