@@ -27,8 +27,9 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, vendor figure
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps; the default is long enough (tens of ms) for the GPU clocks to settle")
     ap.add_argument("--workload", default="cfg2_block768")
     ap.add_argument("--no-extras", action="store_true", help="skip the quantizer-bandwidth and square-GEMM side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -102,10 +103,11 @@ def main():
             nws = tj.workspace_bytes(B.OP_GEMM, A.rows, A.K, Bt.rows)
             if nws == 0:
                 gemm_jobs.append((A, Bt, out, tj.alloc_workspace(16), 2.0 * A.rows * Bt.rows * A.K))
-    for A, Bt, out, ws, _ in gemm_jobs:
-        tj.gemm_nt(A, Bt, B.OUT_BF16, out=out, ws=ws)
+    for _ in range(20):
+        for A, Bt, out, ws, _f in gemm_jobs:
+            tj.gemm_nt(A, Bt, B.OUT_BF16, out=out, ws=ws)
     torch.cuda.synchronize()
-    reps = max(3, min(args.steps, 20))
+    reps = max(3, min(args.steps, 50))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
@@ -140,13 +142,14 @@ def main():
 
 
 def time_events(torch, fn, reps):
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    """Mean duration of fn over reps back-to-back calls, bracketed by two events on the launch stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
     for i in range(reps):
-        ev[i][0].record()
         fn(i)
-        ev[i][1].record()
+    e1.record()
     torch.cuda.synchronize()
-    return sum(a.elapsed_time(b) for a, b in ev) / reps
+    return e0.elapsed_time(e1) / reps
 
 
 def extras(tj, wl, np, torch, dev_bf16):
@@ -172,10 +175,10 @@ def extras(tj, wl, np, torch, dev_bf16):
         "col_sr_with_amax_pass": lambda i: tj.quantize(bufs[i % 4], 1, B.ROUND_SR, outs[i % 2], seed=7, ws=ws),
     }
     for name, fn in cases.items():
-        for i in range(4):
+        for i in range(40):
             fn(i)
         torch.cuda.synchronize()
-        ms = time_events(torch, fn, 20)
+        ms = time_events(torch, fn, 40)
         gbs = alg_bytes / (ms * 1e-3) / 1e9
         res["quant_8192x8192_" + name] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
     # re-quantization of a packed tensor (Q4 / Q6): 0.5625 B in + 0.5625 B out per element
@@ -183,9 +186,10 @@ def extras(tj, wl, np, torch, dev_bf16):
     tj.quantize(bufs[0], 0, B.ROUND_RTN, src, ws=ws)
     dst = tj.alloc_nvfp4(Cc, R)
     fn = lambda i: tj.quantize(src, 1, B.ROUND_SR, dst, seed=7, tensor_id=i)
-    fn(0)
+    for i in range(20):
+        fn(i)
     torch.cuda.synchronize()
-    ms = time_events(torch, fn, 20)
+    ms = time_events(torch, fn, 40)
     gbs = (R * Cc * 9 // 8 + 8) / (ms * 1e-3) / 1e9
     res["requant_col_sr_8192x8192"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
     del bufs
@@ -200,9 +204,10 @@ def extras(tj, wl, np, torch, dev_bf16):
     dW = torch.empty_like(Y)
     gws = tj.alloc_workspace(tj.workspace_bytes(B.OP_GEMM, n, n, n))
     fn = lambda i: tj.gemm_nt(Xq, Wq, B.OUT_BF16, out=Y, ws=gws)
-    fn(0)
+    for i in range(30):
+        fn(i)
     torch.cuda.synchronize()
-    ms = time_events(torch, fn, 10)
+    ms = time_events(torch, fn, 30)
     tf = 2.0 * n ** 3 / (ms * 1e-3) / 1e12
     res["gemm_8192_cubed"] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}
 
@@ -210,9 +215,10 @@ def extras(tj, wl, np, torch, dev_bf16):
         tj.linear_fwd(X, W, B.OUT_BF16, Y=Y, Xq=Xq, Wq=Wq, ws=wsd)
         tj.linear_bwd_dx(dY, Wq, i, 0, B.OUT_BF16, dX=dX, ws=wsd)
         tj.linear_bwd_dw(dY, Xq, i, 0, B.OUT_BF16, dW=dW, ws=wsd)
-    full(0)
+    for i in range(5):
+        full(i)
     torch.cuda.synchronize()
-    ms = time_events(torch, full, 5)
+    ms = time_events(torch, full, 10)
     tf = 3 * 2.0 * n ** 3 / (ms * 1e-3) / 1e12
     res["linear_fwd_bwd_8192_cubed_full_overhead"] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1),
                                                       "frac_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}

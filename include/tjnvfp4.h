@@ -137,6 +137,10 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
  */
 size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_mode);
 
+/* Launch configuration nvfp4_gemm_nt uses for an [M x K] * [N x K]^T product: workgroup tile (rows x columns of the
+ * output) and the number of K splits (> 1 means FP32 partials in ws plus a reduction kernel).  Host-only helper. */
+int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, int *tile_m, int *tile_n, int *split);
+
 /* Tensor maximum of |x| of a bf16 device array of n elements (n % 8 == 0) into amax_out (device [1]). */
 int nvfp4_amax_bf16(const void *src, int64_t n, float *amax_out, void *ws, size_t ws_bytes, void *stream);
 

@@ -25,7 +25,7 @@ OUT_BF16, OUT_F32 = 0, 1
 OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW = 0, 1, 2, 3, 4
 
 EXPORTS = ["nvfp4_quantize", "nvfp4_gemm_nt", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw",
-           "nvfp4_workspace_bytes", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
+           "nvfp4_workspace_bytes", "nvfp4_gemm_plan", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
 
 
 class NVFP4Error(RuntimeError):
@@ -68,6 +68,8 @@ def lib():
         L.nvfp4_linear_bwd_dw.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, vp, sz, vp]
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
+        L.nvfp4_gemm_plan.restype = i32
+        L.nvfp4_gemm_plan.argtypes = [i64, i64, i64, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.nvfp4_amax_bf16.restype = i32
         L.nvfp4_amax_bf16.argtypes = [vp, i64, vp, vp, sz, vp]
         L.nvfp4_stream_key.restype = u64
@@ -124,6 +126,13 @@ def workspace_bytes(op: int, N: int, D: int, Cc: int, outer: int = OUTER_TENSOR)
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
     return torch.empty((max(int(nbytes), 16),), dtype=torch.uint8, device=device)
+
+
+def gemm_plan(M: int, N: int, K: int):
+    """(tile rows, tile columns, K splits) nvfp4_gemm_nt will use for this shape."""
+    a, b, c = C.c_int(), C.c_int(), C.c_int()
+    _check(lib().nvfp4_gemm_plan(M, N, K, C.byref(a), C.byref(b), C.byref(c)), "nvfp4_gemm_plan")
+    return a.value, b.value, c.value
 
 
 def stream_key(seed: int, tensor_id: int) -> int:

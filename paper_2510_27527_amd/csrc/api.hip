@@ -246,6 +246,14 @@ size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_
     }
 }
 
+int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, int *tile_m, int *tile_n, int *split)
+{
+    if (!tile_m || !tile_n || !split) return NVFP4_ERR_NULL;
+    if (M < 0 || N < 0 || K < 0 || K % 64 != 0) return NVFP4_ERR_SHAPE;
+    gemm_plan(M, N, K, tile_m, tile_n, split);
+    return NVFP4_OK;
+}
+
 int nvfp4_amax_bf16(const void *src, int64_t n, float *amax_out, void *ws, size_t ws_bytes, void *stream)
 {
     if (!src || !amax_out) return NVFP4_ERR_NULL;

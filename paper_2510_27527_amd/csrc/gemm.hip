@@ -63,15 +63,16 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
 // Global -> LDS copies that bypass registers: every lane supplies a global address, the wave's data
 // lands at lds_addr + lane * 16 (or * 4).  Written as inline assembly so that completion is tracked only
 // by the explicit s_waitcnt vmcnt(n) of the pipeline (the compiler would otherwise wait for every
-// outstanding copy before each LDS read).  lds_addr must be wave-uniform.
+// outstanding copy before each LDS read).  lds_addr must be wave-uniform; the s_nop covers the wait state
+// between a scalar write of M0 and the copy that uses it.
 // The global address is a wave-uniform 64-bit base plus a 32-bit unsigned byte offset per lane.
 __device__ __forceinline__ void lds_dma16(const void *base, uint32_t off, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma4(const void *base, uint32_t off, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
 }
 
 __device__ __forceinline__ uint32_t pick(uint4 v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
@@ -359,10 +360,11 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *__
 
 // ---- host side: tile shape and split choice ---------------------------------------------------
 
-struct TileCfg { int tm, tn; double eff; };
-// relative MFMA efficiency of a workgroup tile: the FP4 -> FP16 expansion is per fragment, the MFMA
-// work per fragment pair, so larger wave tiles amortise the expansion better
-const TileCfg kTiles[] = {{4, 4, 1.00}, {4, 2, 0.80}, {2, 4, 0.80}, {2, 2, 0.55}};
+// Tile shapes and a small cost model (microseconds, from timings of this kernel on MI355X) that picks
+// the tile and the number of K splits for a problem.
+struct TileCfg { int tm, tn; double t_stage; double t_fixed; int occupancy; };
+// t_stage: one 128-k pipeline stage of one workgroup with the CU to itself; t_fixed: prologue + epilogue
+const TileCfg kTiles[] = {{4, 4, 3.2, 6.0, 1}, {4, 2, 2.0, 5.0, 1}, {2, 4, 2.0, 5.0, 1}, {2, 2, 1.5, 5.0, 3}};
 constexpr int kNumCU = 256;
 constexpr int kNC = 2;
 
@@ -376,14 +378,19 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
     for (int t = 0; t < 4; ++t) {
         const int64_t bm = 64 * kTiles[t].tm, bn = 64 * kTiles[t].tn;
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-        for (int split = 1; split <= 16; split *= 2) {
+        for (int split = 1; split <= 16; ++split) {
             if (split > 1 && chunks / split < 8) break;
             const int64_t cps = (chunks + split - 1) / split;
+            if (split > 1 && (chunks + cps - 1) / cps != split) continue;      // same launch as a smaller split
             const int64_t wgs = tiles * split;
-            const int64_t rounds = (wgs + kNumCU - 1) / kNumCU;
-            // time ~ rounds * work of one workgroup / efficiency (+ fixed cost per round, + the reduction pass)
-            double time = (double)rounds * ((double)(bm * bn) * (double)(cps * 64) / kTiles[t].eff + 4.0e6);
-            if (split > 1) time += (double)(M * N) * (double)split * 6.0 / kNumCU * 4.0;
+            const double stages = (double)((cps + kNC - 1) / kNC);
+            // workgroups sharing a CU slow each other down (128 x 128 tiles: up to three per CU)
+            const int64_t per_cu = (wgs + kNumCU - 1) / kNumCU;
+            const int64_t conc = per_cu < kTiles[t].occupancy ? per_cu : kTiles[t].occupancy;
+            const double slow = conc == 1 ? 1.0 : conc == 2 ? 1.75 : 2.35;
+            const int64_t waves = (wgs + kNumCU * conc - 1) / (kNumCU * conc);
+            double time = (double)waves * (stages * kTiles[t].t_stage * slow + kTiles[t].t_fixed);
+            if (split > 1) time += 4.0 + (double)(split + 1) * (double)(M * N) * 4.0 / 3.5e6;   // partials out and back in
             if (time < best_t) { best_t = time; best = Plan{t, split, (int)cps}; }
         }
     }
@@ -420,6 +427,14 @@ hipError_t launch_tile(int tile, const GemmArgs &g, dim3 grid, hipStream_t st)
 }
 
 }  // namespace
+
+void gemm_plan(int64_t M, int64_t N, int64_t K, int *bm, int *bn, int *split)
+{
+    const Plan p = make_plan(M, N, K);
+    *bm = 64 * kTiles[p.tile].tm;
+    *bn = 64 * kTiles[p.tile].tn;
+    *split = p.split;
+}
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {

@@ -61,6 +61,8 @@ struct GemmOperand {
 
 // Out[M x N] = A[M x K] * B[N x K]^T; splitk_ws holds split * M * N floats when split > 1
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+// workgroup tile and K split the launcher will use for this shape
+void gemm_plan(int64_t M, int64_t N, int64_t K, int *bm, int *bn, int *split);
 hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K, void *out, int out_f32,
                           void *ws, size_t ws_bytes, hipStream_t st);
 
