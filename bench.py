@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="cfg2_block768")
     ap.add_argument("--no-extras", action="store_true", help="skip the quantizer-bandwidth and square-GEMM side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device copy of 1 GiB five times (reference point for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -46,12 +48,22 @@ def main():
     import numpy as np
     import torch
 
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "copy_calibration_bytes_written": src.numel() * 4,
+                          "launches": 5}))
+        return
+
     import paper_2510_27527_amd as tj
     import workloads as wl
     B = tj.binding
     B.lib()
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
 
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
@@ -118,9 +130,15 @@ def main():
     gemm_ms = e0.elapsed_time(e1) / (reps * len(gemm_jobs))
     gemm_flops = sum(j[4] for j in gemm_jobs) / len(gemm_jobs)
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+    traffic = None    # HBM bytes per launch from the committed rocprofv3 counter summary of this same command
+    tpath = os.path.join(ROOT, "profiles", "gemm_quant_cfg2_block768_hbm_traffic.txt")
+    if args.workload == "cfg2_block768" and os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch="):
+                traffic = int(line.split("=")[1])
     roofline = {"kernel": "gemm_nt_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4),
-                "traffic": None, "avg_launch_ms": round(gemm_ms, 5), "flops_per_launch": gemm_flops,
+                "traffic": traffic, "avg_launch_ms": round(gemm_ms, 5), "flops_per_launch": gemm_flops,
                 "launches_timed": reps * len(gemm_jobs),
                 "note": "mean over the %d single-launch products of a step (2*M*N*K flops each)" % len(gemm_jobs)}
 
@@ -226,25 +244,28 @@ def extras(tj, wl, np, torch, dev_bf16):
 
 
 def cpu_baseline(wl, np, workload):
-    """The CPU oracle, as it stands, on a bounded sample: the block's largest linear on (at most) 8192
-    tokens, all six quantizations and the three float64 products, on all host threads."""
+    """The CPU oracle, as it stands, on a bounded sample of the workload: every linear of the block on (at most)
+    8192 tokens - all six quantizations and the three float64 products each - on all host threads."""
     import oracle
-    lin = [l for l in wl.config_linears(workload)]
-    name, N, D, C, seed, kind = max(lin, key=lambda l: l[2] * l[3])
-    n = min(N, 8192)
-    while 3 * 2.0 * n * D * C > 1.5e11 and n > 256:       # keep the sample to roughly 10-30 s of CPU work
-        n //= 2
-    Xb, Wb, dYb = wl.linear_inputs(n, D, C, seed, kind)
     oracle.lib()
-    t0 = time.perf_counter()
-    Xq, Wq = oracle.linear_fwd(Xb, Wb)
-    oracle.gemm_nt(Xq, Wq)
-    a, b = oracle.linear_bwd_dx_operands(dYb, Wq, 0, 0)
-    oracle.gemm_nt(a, b)
-    a, b = oracle.linear_bwd_dw_operands(dYb, Xq, 0, 0)
-    oracle.gemm_nt(a, b)
-    dt = time.perf_counter() - t0
-    flops = 3 * 2.0 * n * D * C
+    flops = 0.0
+    names = []
+    dt = 0.0
+    for name, N, D, C, seed, kind in wl.config_linears(workload):
+        n = min(N, 8192)
+        if 3 * 2.0 * n * D * C > 1.5e11:
+            continue                                   # keep the sample to roughly 10 s of CPU work
+        Xb, Wb, dYb = wl.linear_inputs(n, D, C, seed, kind)
+        t0 = time.perf_counter()
+        Xq, Wq = oracle.linear_fwd(Xb, Wb)
+        oracle.gemm_nt(Xq, Wq)
+        a, b = oracle.linear_bwd_dx_operands(dYb, Wq, 0, 0)
+        oracle.gemm_nt(a, b)
+        a, b = oracle.linear_bwd_dw_operands(dYb, Xq, 0, 0)
+        oracle.gemm_nt(a, b)
+        dt += time.perf_counter() - t0
+        flops += 3 * 2.0 * n * D * C
+        names.append("%s %d->%d x %d tokens" % (name, D, C, n))
     try:
         cores = len(os.sched_getaffinity(0))
     except Exception:
@@ -254,7 +275,7 @@ def cpu_baseline(wl, np, workload):
         cores = min(cores, int(omp))
     return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "seconds": round(dt, 2),
-            "sample": "linear '%s' %d->%d on %d of %d tokens: 6 quantizations + 3 float64 products" % (name, D, C, n, N)}
+            "sample": "oracle fwd+bwd (6 quantizations + 3 float64 products per linear) of: " + "; ".join(names)}
 
 
 if __name__ == "__main__":
