@@ -81,7 +81,10 @@ __device__ __forceinline__ uint32_t pick(uint4 v, int i) { return i == 0 ? v.x :
 // 64 k per pipeline stage, three stage buffers in LDS.  Codes and scale bytes go global -> LDS
 // directly (a wave instruction fills 64 consecutive 16-byte / 4-byte slots), two stages ahead.
 //   codes : slot of (row, 16-byte piece p of the stage's row segment) = row * SLOTS + (p ^ swz(row))
-//   scales: dword of (chunk c, row) = c * ROWS + row   (A rows first, then B rows)
+//   scales: dword of (chunk c, row) = c * ROWS + row   (A rows first, then B rows); when K is a multiple of 256
+//           (PS = true) scale bytes are instead fetched 16 per row (four chunks = two stages) into a ring of
+//           three [ROWS][16] buffers, half of the rows per stage, four stages ahead: one 16-byte request per
+//           row and 256 k instead of four 4-byte requests
 // The reduction is a software pipeline over 16-wide k steps: while the MFMAs of step g run, the
 // FP4 -> FP16 expansion of step g + 1 is issued (about four VALU instructions per MFMA), and the
 // raw codes of the next chunk are fetched from LDS one step earlier.  One barrier per stage, placed
@@ -91,27 +94,27 @@ __device__ __forceinline__ uint32_t pick(uint4 v, int i) { return i == 0 ? v.x :
 template <int TM, int TN>
 struct RawFrags {
     uint4 qa[TM], qb[TN];       // 32 codes per fragment
-    uint32_t sa[TM], sb[TN];    // the chunk's four scale bytes per fragment row
-    uint32_t live;              // 0xFF, or 0 for a chunk past the end of K (its scales count as zero)
 };
 template <int TM, int TN>
 struct OpFrags {
     half8_t a[TM], b[TN];
 };
 
-template <int TM, int TN, int NC, int OUT>   // OUT: 0 bf16, 1 f32, 2 raw f32 split-K partial
+template <int TM, int TN, int NC, int OUT, bool PS>   // OUT: 0 bf16, 1 f32, 2 raw f32 split-K partial
 __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kernel(GemmArgs g)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN, ROWS = BM + BN;
     constexpr int SLOTS = 2 * NC;                       // 16-byte pieces per row per stage
     constexpr int A_SLOTS = BM * SLOTS, B_SLOTS = BN * SLOTS;
-    constexpr int LA = A_SLOTS / kThreads, LB = B_SLOTS / kThreads, LS = ROWS * NC / kThreads;
-    constexpr int NLOAD = LA + LB + LS;                  // direct-to-LDS loads per thread per stage
-    constexpr int CODE_BYTES = (A_SLOTS + B_SLOTS) * 16;
-    constexpr int STAGE_BYTES = CODE_BYTES + ROWS * NC * 4;
+    constexpr int LA = A_SLOTS / kThreads, LB = B_SLOTS / kThreads, LS = PS ? 0 : ROWS * NC / kThreads;
+    constexpr int NLOAD = LA + LB + (PS ? 1 : LS);       // direct-to-LDS loads per thread per stage
+    constexpr int CODE_BYTES = (A_SLOTS + B_SLOTS) * 16; // one stage of codes; three of them, then the scales
+    constexpr int SC_BYTES = PS ? ROWS * 16 : ROWS * NC * 4;   // one scale buffer (a pair of stages / one stage)
+    constexpr int SC_BASE = 3 * CODE_BYTES;
     constexpr int STEPS = NC * 4;
+    static_assert(!PS || NC == 2, "paired scale fetch assumes two chunks per stage");
     static_assert(NC % 2 == 0, "chunk parity must repeat per stage");
-    static_assert(LA >= 1 && LB >= 1 && LS >= 1 && (ROWS * NC) % kThreads == 0, "tile too small");
+    static_assert(LA >= 1 && LB >= 1 && (PS || LS >= 1) && (ROWS * NC) % kThreads == 0, "tile too small");
     static_assert(NLOAD <= 15, "vmcnt immediate below assumes at most 15 loads per stage");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
     if (nchunks > 0) {
         // Per-lane constants of the loads: 32-bit byte offsets from the tile's (uniform) base pointers, the
         // piece / chunk index each load covers, and a bit mask of the loads whose row exists.
-        uint32_t coff[LA + LB], soff[LS];
+        uint32_t coff[LA + LB], soff[PS ? 2 : LS];
         uint32_t cpieces = 0, schunks = 0, rowmask = 0;      // 4 bits per load / 1 bit per load
 #pragma unroll
         for (int u = 0; u < LA + LB; ++u) {
@@ -168,13 +171,24 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
             cpieces |= (uint32_t)piece << (4 * u);
             if ((isA ? m0 : n0) + row < (isA ? g.M : g.N)) rowmask |= 1u << u;
         }
+        if (!PS) {
 #pragma unroll
-        for (int u = 0; u < LS; ++u) {
-            const int q = u * 4 + wave, c = q / (ROWS / 64), row = (q % (ROWS / 64)) * 64 + lane;
-            const bool isA = row < BM;
-            soff[u] = (uint32_t)(isA ? row : row - BM) * (uint32_t)sstride + (uint32_t)c * 4u;
-            schunks |= (uint32_t)c << (4 * u);
-            if ((isA ? m0 + row : n0 + row - BM) < (isA ? g.M : g.N)) rowmask |= 1u << (LA + LB + u);
+            for (int u = 0; u < LS; ++u) {
+                const int q = u * 4 + wave, c = q / (ROWS / 64), row = (q % (ROWS / 64)) * 64 + lane;
+                const bool isA = row < BM;
+                soff[u] = (uint32_t)(isA ? row : row - BM) * (uint32_t)sstride + (uint32_t)c * 4u;
+                schunks |= (uint32_t)c << (4 * u);
+                if ((isA ? m0 + row : n0 + row - BM) < (isA ? g.M : g.N)) rowmask |= 1u << (LA + LB + u);
+            }
+        } else {
+            // half h of a pair: wave-instruction q = 4 h + wave covers rows (q % (ROWS/64)) * 64 .. + 63
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = ((h * 4 + wave) % (ROWS / 64)) * 64 + lane;
+                const bool isA = row < BM;
+                const bool ok = (isA ? m0 + row : n0 + row - BM) < (isA ? g.M : g.N);
+                soff[h] = ok ? (uint32_t)(isA ? row : row - BM) * (uint32_t)sstride : 0u;
+            }
         }
         const bool tile_full = m0 + BM <= g.M && n0 + BN <= g.N;
         const uint8_t *a_cbase = g.a_codes + m0 * cstride + cbeg * 32, *b_cbase = g.b_codes + n0 * cstride + cbeg * 32;
@@ -185,7 +199,8 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
         // bytes: missing rows are never stored, late chunks get zero scales when they are read).
         auto issue_loads = [&](int kt, int buf) {
             const int64_t c0 = (int64_t)kt * NC;                  // first chunk of the stage, relative to cbeg
-            const uint32_t dst = lds_base + buf * STAGE_BYTES;
+            const uint32_t dst = lds_base + buf * CODE_BYTES;
+            const uint32_t sdst = lds_base + SC_BASE + buf * SC_BYTES;
             const uint8_t *ac = a_cbase + c0 * 32, *bc = b_cbase + c0 * 32;
             const uint8_t *as = a_sbase + c0 * 4, *bs = b_sbase + c0 * 4;
             if (tile_full && c0 + NC <= nchunks) {
@@ -197,7 +212,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
 #pragma unroll
                 for (int u = 0; u < LS; ++u) {
                     const int q = u * 4 + wave;
-                    lds_dma4((q % (ROWS / 64)) * 64 < BM ? as : bs, soff[u], dst + CODE_BYTES + q * 256);
+                    lds_dma4((q % (ROWS / 64)) * 64 < BM ? as : bs, soff[u], sdst + q * 256);
                 }
             } else {
                 // Same number of instructions (the pipeline counts them with vmcnt); loads that have nothing
@@ -218,36 +233,63 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
                     const int64_t c = c0 + ((schunks >> (4 * u)) & 15);
                     const bool ok = ((rowmask >> (LA + LB + u)) & 1u) && c < nchunks;
                     lds_dma4(stage_ok ? (isA ? as : bs) : (isA ? a_sbase : b_sbase), ok ? soff[u] : 0u,
-                             dst + CODE_BYTES + q * 256);
+                             sdst + q * 256);
                 }
             }
         };
+        // PS: half h of scale pair P (16 scale bytes = 256 k per row) into pair buffer P % 3; pairs past the end
+        // re-fetch pair 0 (valid memory, never consumed)
+        const int npairs = nchunks / 4;
+        auto issue_scale_half = [&](int P, int h) {
+            const int rb = (h * 4 + wave) % (ROWS / 64);
+            const bool isA = rb * 64 < BM;
+            const int Pl = P < npairs ? P : 0;
+            const uint8_t *base = (isA ? a_sbase : b_sbase) + (int64_t)Pl * 16;
+            lds_dma16(base, soff[h], lds_base + SC_BASE + (P % 3) * SC_BYTES + rb * 64 * 16);
+        };
 
-        auto read_raw = [&](RawFrags<TM, TN> &r, int buf, int c, bool live) {
-            const uint4 *codes = reinterpret_cast<const uint4 *>(smem_raw + buf * STAGE_BYTES);
-            const uint32_t *scales = reinterpret_cast<const uint32_t *>(smem_raw + buf * STAGE_BYTES + CODE_BYTES) + c * ROWS;
+        uint32_t scA[NC][TM], scB[NC][TN];   // four scale bytes per chunk and fragment row
+        uint32_t live[NC];                    // 0xFF, or 0 for a chunk past the end of K (its scales count as zero)
+        auto read_raw = [&](RawFrags<TM, TN> &r, int buf, int c, bool is_live) {
+            const uint4 *codes = reinterpret_cast<const uint4 *>(smem_raw + buf * CODE_BYTES);
+            const uint32_t *scales = reinterpret_cast<const uint32_t *>(smem_raw + SC_BASE + buf * SC_BYTES) + c * ROWS;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = (wm * TM + i) * 32 + lr;
                 r.qa[i] = codes[row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
-                r.sa[i] = scales[row];
+                if (!PS) scA[c][i] = scales[row];
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int row = (wn * TN + j) * 32 + lr;
                 r.qb[j] = codes[A_SLOTS + row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
-                r.sb[j] = scales[BM + row];
+                if (!PS) scB[c][j] = scales[BM + row];
             }
-            r.live = live ? 0xFFu : 0u;
+            if (!PS) live[c] = is_live ? 0xFFu : 0u;
+        };
+        // PS: the two chunk dwords of stage kt for every fragment row (second half of the pair for odd stages)
+        auto read_stage_scales = [&](int kt) {
+            const uint2 *sp = reinterpret_cast<const uint2 *>(smem_raw + SC_BASE + ((kt >> 1) % 3) * SC_BYTES) + (kt & 1);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const uint2 v = sp[((wm * TM + i) * 32 + lr) * 2];
+                scA[0][i] = v.x; scA[1][i] = v.y;
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const uint2 v = sp[(BM + (wn * TN + j) * 32 + lr) * 2];
+                scB[0][j] = v.x; scB[1][j] = v.y;
+            }
         };
 
         half2_t fA[TM], fB[TN];
-        auto expand = [&](OpFrags<TM, TN> &o, const RawFrags<TM, TN> &r, int ks) {
+        auto expand = [&](OpFrags<TM, TN> &o, const RawFrags<TM, TN> &r, int c, int ks) {
             if ((ks & 1) == 0) {
+                const uint32_t mask = PS ? 0xFFu : live[c];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) fA[i] = scale_pair((r.sa[i] >> (16 * kg + 4 * ks)) & r.live);
+                for (int i = 0; i < TM; ++i) fA[i] = scale_pair((scA[c][i] >> (16 * kg + 4 * ks)) & mask);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) fB[j] = scale_pair((r.sb[j] >> (16 * kg + 4 * ks)) & r.live);
+                for (int j = 0; j < TN; ++j) fB[j] = scale_pair((scB[c][j] >> (16 * kg + 4 * ks)) & mask);
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) o.a[i] = expand8(pick(r.qa[i], ks), fA[i]);
@@ -259,16 +301,25 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
         OpFrags<TM, TN> op[2];
 
         issue_loads(0, 0);
-        issue_loads(1, 1);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | NLOAD);       // vmcnt(NLOAD): stage 0 has landed
+        if (PS) {
+            issue_scale_half(0, 0); issue_scale_half(0, 1);
+            issue_scale_half(1, 0); issue_scale_half(1, 1);
+            issue_loads(1, 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (LA + LB));   // everything but stage 1's codes has landed
+        } else {
+            issue_loads(1, 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70 | NLOAD);       // vmcnt(NLOAD): stage 0 has landed
+        }
         __syncthreads();
+        if (PS) read_stage_scales(0);
         read_raw(raw[0], 0, 0, true);
-        expand(op[0], raw[0], 0);
+        expand(op[0], raw[0], 0, 0);
 
         int buf = 0;
         for (int kt = 0; kt < nk; ++kt) {
             const int nbuf = buf == 2 ? 0 : buf + 1;
             issue_loads(kt + 2, nbuf == 2 ? 0 : nbuf + 1);
+            if (PS) issue_scale_half((kt >> 1) + 2, kt & 1);
 #pragma unroll
             for (int gs = 0; gs < STEPS; ++gs) {
                 const int c = gs / 4, ks = gs % 4;
@@ -276,10 +327,11 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
                 if (gs == STEPS - 2) {
                     __builtin_amdgcn_s_waitcnt(0x0F70 | NLOAD);   // all but the newest stage's loads: stage kt+1 has landed
                     __syncthreads();
+                    if (PS) read_stage_scales(kt + 1);
                     read_raw(raw[0], nbuf, 0, (kt + 1) * NC < nchunks);
                 }
-                if (gs + 1 < STEPS) expand(op[(gs + 1) & 1], raw[((gs + 1) / 4) & 1], (gs + 1) % 4);
-                else expand(op[0], raw[0], 0);
+                if (gs + 1 < STEPS) expand(op[(gs + 1) & 1], raw[((gs + 1) / 4) & 1], (gs + 1) / 4, (gs + 1) % 4);
+                else expand(op[0], raw[0], 0, 0);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -291,7 +343,10 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
 #pragma unroll
                 for (int q = 0; q < TM * TN; ++q) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    if (fetch && q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    if (fetch && q < TM + TN) {
+                        if (PS && gs != STEPS - 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        else __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    }
                     __builtin_amdgcn_sched_group_barrier(0x002, (8 * (TM + TN) + TM * TN - 1) / (TM * TN) + 1, 0);
                 }
             }
@@ -380,7 +435,8 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         for (int split = 1; split <= 16; ++split) {
             if (split > 1 && chunks / split < 8) break;
-            const int64_t cps = (chunks + split - 1) / split;
+            int64_t cps = (chunks + split - 1) / split;
+            if (chunks % 4 == 0) cps = (cps + 3) / 4 * 4;                       // splits on 256-k boundaries
             if (split > 1 && (chunks + cps - 1) / cps != split) continue;      // same launch as a smaller split
             const int64_t wgs = tiles * split;
             const double stages = (double)((cps + kNC - 1) / kNC);
@@ -398,12 +454,12 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
     return best;
 }
 
-template <int TM, int TN, int OUT>
+template <int TM, int TN, int OUT, bool PS>
 hipError_t launch_cfg(const GemmArgs &g, dim3 grid, hipStream_t st)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int lds = 3 * ((BM + BN) * 2 * kNC * 16 + (BM + BN) * kNC * 4);
-    auto kern = gemm_nt_kernel<TM, TN, kNC, OUT>;
+    constexpr int lds = 3 * ((BM + BN) * 2 * kNC * 16 + (BM + BN) * (PS ? 16 : kNC * 4));
+    auto kern = gemm_nt_kernel<TM, TN, kNC, OUT, PS>;
     static bool attr_set = false;
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -415,14 +471,14 @@ hipError_t launch_cfg(const GemmArgs &g, dim3 grid, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int OUT>
+template <int OUT, bool PS>
 hipError_t launch_tile(int tile, const GemmArgs &g, dim3 grid, hipStream_t st)
 {
     switch (tile) {
-        case 0: return launch_cfg<4, 4, OUT>(g, grid, st);
-        case 1: return launch_cfg<4, 2, OUT>(g, grid, st);
-        case 2: return launch_cfg<2, 4, OUT>(g, grid, st);
-        default: return launch_cfg<2, 2, OUT>(g, grid, st);
+        case 0: return launch_cfg<4, 4, OUT, PS>(g, grid, st);
+        case 1: return launch_cfg<4, 2, OUT, PS>(g, grid, st);
+        case 2: return launch_cfg<2, 4, OUT, PS>(g, grid, st);
+        default: return launch_cfg<2, 2, OUT, PS>(g, grid, st);
     }
 }
 
@@ -462,8 +518,15 @@ hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K,
     const int split = p.split > 1 ? (int)((chunks + p.chunks_per_split - 1) / p.chunks_per_split) : 1;
     g.out = split > 1 ? ws : out;
     dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)split);
-    hipError_t e = split > 1 ? launch_tile<2>(p.tile, g, grid, st)
-                   : out_f32 ? launch_tile<1>(p.tile, g, grid, st) : launch_tile<0>(p.tile, g, grid, st);
+    // K a multiple of 256 with splits on 256-boundaries: scale bytes are fetched 16 per row
+    const bool ps = K % 256 == 0 && p.chunks_per_split % 4 == 0;
+    hipError_t e;
+    if (ps)
+        e = split > 1 ? launch_tile<2, true>(p.tile, g, grid, st)
+            : out_f32 ? launch_tile<1, true>(p.tile, g, grid, st) : launch_tile<0, true>(p.tile, g, grid, st);
+    else
+        e = split > 1 ? launch_tile<2, false>(p.tile, g, grid, st)
+            : out_f32 ? launch_tile<1, false>(p.tile, g, grid, st) : launch_tile<0, false>(p.tile, g, grid, st);
     if (e != hipSuccess) return e;
     if (split > 1) {
         const int64_t mn = M * N;
