@@ -78,7 +78,7 @@ def main():
         L["Y"] = torch.empty((N, C), dtype=torch.bfloat16, device=dev)
         L["dX"] = torch.empty((N, D), dtype=torch.bfloat16, device=dev)
         L["dW"] = torch.empty((C, D), dtype=torch.bfloat16, device=dev)
-        nbytes = max(tj.workspace_bytes(op, N, D, C) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD_DX, B.OP_LINEAR_BWD_DW))
+        nbytes = max(tj.workspace_bytes(op, N, D, C) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD))
         L["ws"] = tj.alloc_workspace(nbytes)
         layers.append(L)
     flops_step = wl.config_flops(args.workload)
@@ -87,8 +87,7 @@ def main():
         for L in layers:
             tj.linear_fwd(L["X"], L["W"], B.OUT_BF16, Y=L["Y"], Xq=L["Xq"], Wq=L["Wq"], ws=L["ws"])
         for L in reversed(layers):
-            tj.linear_bwd_dx(L["dY"], L["Wq"], sr_seed, L["li"], B.OUT_BF16, dX=L["dX"], ws=L["ws"])
-            tj.linear_bwd_dw(L["dY"], L["Xq"], sr_seed, L["li"], B.OUT_BF16, dW=L["dW"], ws=L["ws"])
+            tj.linear_bwd(L["dY"], L["Xq"], L["Wq"], sr_seed, L["li"], B.OUT_BF16, dX=L["dX"], dW=L["dW"], ws=L["ws"])
 
     for i in range(args.warmup):
         step(i)
@@ -217,7 +216,7 @@ def extras(tj, wl, np, torch, dev_bf16):
     Xb, Wb, dYb = wl.linear_inputs(n, n, n, wl.CONFIGS["cfg5_square8192"]["seed"], "square")
     X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
     Y, Xq, Wq = tj.linear_fwd(X, W)
-    wsd = tj.alloc_workspace(max(tj.workspace_bytes(op, n, n, n) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD_DX, B.OP_LINEAR_BWD_DW)))
+    wsd = tj.alloc_workspace(max(tj.workspace_bytes(op, n, n, n) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD)))
     dX = torch.empty_like(Y)
     dW = torch.empty_like(Y)
     gws = tj.alloc_workspace(tj.workspace_bytes(B.OP_GEMM, n, n, n))
@@ -231,8 +230,7 @@ def extras(tj, wl, np, torch, dev_bf16):
 
     def full(i):
         tj.linear_fwd(X, W, B.OUT_BF16, Y=Y, Xq=Xq, Wq=Wq, ws=wsd)
-        tj.linear_bwd_dx(dY, Wq, i, 0, B.OUT_BF16, dX=dX, ws=wsd)
-        tj.linear_bwd_dw(dY, Xq, i, 0, B.OUT_BF16, dW=dW, ws=wsd)
+        tj.linear_bwd(dY, Xq, Wq, i, 0, B.OUT_BF16, dX=dX, dW=dW, ws=wsd)
     for i in range(5):
         full(i)
     torch.cuda.synchronize()

@@ -62,7 +62,7 @@ enum { NVFP4_OUTER_TENSOR = 0, NVFP4_OUTER_BLOCK128 = 1 };       /* Sec. 2.2 out
 enum { NVFP4_SRC_BF16 = 0, NVFP4_SRC_NVFP4 = 1 };                 /* source kind of nvfp4_quantize         */
 enum { NVFP4_OUT_BF16 = 0, NVFP4_OUT_F32 = 1 };                   /* output element type of the products   */
 enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_GEMM = 1, NVFP4_OP_LINEAR_FWD = 2,
-       NVFP4_OP_LINEAR_BWD_DX = 3, NVFP4_OP_LINEAR_BWD_DW = 4 };
+       NVFP4_OP_LINEAR_BWD_DX = 3, NVFP4_OP_LINEAR_BWD_DW = 4, NVFP4_OP_LINEAR_BWD = 5 };
 
 /* One quantized operand.  The caller fills the four pointers with buffers of the
  * sizes given above; the producing call fills rows, K and outer_mode. */
@@ -130,6 +130,16 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
 int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C,
                         void *dW, int out_dtype, uint64_t seed, uint32_t layer_id,
                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Both gradients of one layer in one call (Sec. 2.3, second and third line).  Same results, byte for byte, as
+ * nvfp4_linear_bwd_dx followed by nvfp4_linear_bwd_dw with the same seed and layer_id, but dY is read once for its
+ * maximum and once more for both of its quantizations (Q3 row-wise and Q5 column-wise leave one kernel).
+ * Needs C % 64 == 0 and N % 64 == 0.
+ */
+int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx,
+                     int64_t N, int64_t D, int64_t C, void *dX, void *dW, int out_dtype,
+                     uint64_t seed, uint32_t layer_id, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Scratch bytes an operation needs.  op = NVFP4_OP_*.  QUANTIZE: (N, D) = (R, C) of the source, C ignored.

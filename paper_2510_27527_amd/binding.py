@@ -22,9 +22,9 @@ SCALE_DEFAULT, SCALE_NE, SCALE_UP = 0, 1, 2
 OUTER_TENSOR, OUTER_BLOCK128 = 0, 1
 SRC_BF16, SRC_NVFP4 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
-OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW = 0, 1, 2, 3, 4
+OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW, OP_LINEAR_BWD = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ["nvfp4_quantize", "nvfp4_gemm_nt", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw",
+EXPORTS = ["nvfp4_quantize", "nvfp4_gemm_nt", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd",
            "nvfp4_workspace_bytes", "nvfp4_gemm_plan", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
 
 
@@ -66,6 +66,9 @@ def lib():
         L.nvfp4_linear_bwd_dx.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, vp, sz, vp]
         L.nvfp4_linear_bwd_dw.restype = i32
         L.nvfp4_linear_bwd_dw.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, vp, sz, vp]
+        L.nvfp4_linear_bwd.restype = i32
+        L.nvfp4_linear_bwd.argtypes = [vp, C.POINTER(CTensor), C.POINTER(CTensor), i64, i64, i64, vp, vp, i32, u64, u32,
+                                       vp, sz, vp]
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
         L.nvfp4_gemm_plan.restype = i32
@@ -235,3 +238,19 @@ def linear_bwd_dw(dY: torch.Tensor, Xq: NVFP4Tensor, seed: int, layer_id: int, o
                                    _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_linear_bwd_dw")
     return dW
+
+
+def linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
+               dX: Optional[torch.Tensor] = None, dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """nvfp4_linear_bwd: both gradients, dY read once for its maximum and once for both quantizations."""
+    N, Cc = dY.shape
+    D = Xq.K
+    dev = dY.device
+    dX = _out_tensor(N, D, out_dtype, dev) if dX is None else dX
+    dW = _out_tensor(Cc, D, out_dtype, dev) if dW is None else dW
+    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD, N, D, Cc), dev) if ws is None else ws
+    cx, cw = Xq.c_struct(), Wq.c_struct()
+    rc = lib().nvfp4_linear_bwd(_ptr(dY), C.byref(cx), C.byref(cw), N, D, Cc, _ptr(dX), _ptr(dW), out_dtype, seed,
+                                layer_id, _ptr(ws), ws.numel(), _stream())
+    _check(rc, "nvfp4_linear_bwd")
+    return dX, dW

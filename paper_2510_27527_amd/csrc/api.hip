@@ -242,6 +242,11 @@ size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_
             return partials_bytes() + packed_bytes(N, C) + packed_bytes(D, C) + align_up(gemm_workspace_bytes(N, D, C));
         case NVFP4_OP_LINEAR_BWD_DW:
             return partials_bytes() + packed_bytes(C, N) + packed_bytes(D, N) + align_up(gemm_workspace_bytes(C, D, N));
+        case NVFP4_OP_LINEAR_BWD: {
+            const size_t g1 = align_up(gemm_workspace_bytes(N, D, C)), g2 = align_up(gemm_workspace_bytes(C, D, N));
+            return partials_bytes() + align_up(sizeof(float)) + packed_bytes(N, C) + packed_bytes(D, C) +
+                   packed_bytes(C, N) + packed_bytes(D, N) + (g1 > g2 ? g1 : g2);
+        }
         default: return 0;
     }
 }
@@ -403,6 +408,77 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
     rc = run_quantize(Xq_ctx, p6, &c6, &Xq2, nullptr, st);
     if (rc) return rc;
     return run_gemm(&dYq, &Xq2, dW, out_dtype, gws, gbytes, st);
+}
+
+int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D,
+                     int64_t C, void *dX, void *dW, int out_dtype, uint64_t seed, uint32_t layer_id, void *ws,
+                     size_t ws_bytes, void *stream)
+{
+    if (!dY || !Xq_ctx || !Wq_ctx) return NVFP4_ERR_NULL;
+    if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
+    if (C % 64 != 0 || N % 64 != 0) return NVFP4_ERR_SHAPE;
+    int rc = check_out(dX, out_dtype);
+    if (rc) return rc;
+    rc = check_out(dW, out_dtype);
+    if (rc) return rc;
+    if (Wq_ctx->rows != C || Wq_ctx->K != D || Xq_ctx->rows != N || Xq_ctx->K != D) return NVFP4_ERR_MISMATCH;
+    if (!aligned16(dY)) return NVFP4_ERR_ALIGN;
+    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD, N, D, C, NVFP4_OUTER_TENSOR))
+        return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
+    Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
+    float *part = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
+    float *amax = static_cast<float *>(cv.take(sizeof(float)));
+    nvfp4_tensor q3{}, q4{}, q5{}, q6{};
+    if (!carve_tensor(cv, N, C, &q3) || !carve_tensor(cv, D, C, &q4) || !carve_tensor(cv, C, N, &q5) ||
+        !carve_tensor(cv, D, N, &q6))
+        return NVFP4_ERR_WORKSPACE;
+    const size_t g1 = gemm_workspace_bytes(N, D, C), g2 = gemm_workspace_bytes(C, D, N);
+    const size_t gbytes = g1 > g2 ? g1 : g2;
+    void *gws = gbytes ? cv.take(gbytes) : nullptr;
+
+    nvfp4_qcfg c[4];
+    for (int k = 0; k < 4; ++k) {
+        c[k] = nvfp4_qcfg{};
+        c[k].rounding = NVFP4_ROUND_SR;
+        c[k].outer_mode = NVFP4_OUTER_TENSOR;
+        c[k].seed = seed;
+        c[k].tensor_id = layer_id * 8u + 3u + (uint32_t)k;
+    }
+    c[0].amax_in = amax;     // Q3 and Q5 share the maximum of dY
+    c[2].amax_in = amax;
+    QuantPlan p3{}, p4{}, p5{}, p6{};
+    rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 0, &c[0], &q3, &p3);
+    if (rc) return rc;
+    rc = plan_quantize(Wq_ctx, NVFP4_SRC_NVFP4, C, D, 1, &c[1], &q4, &p4);
+    if (rc) return rc;
+    rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 1, &c[2], &q5, &p5);
+    if (rc) return rc;
+    rc = plan_quantize(Xq_ctx, NVFP4_SRC_NVFP4, N, D, 1, &c[3], &q6, &p6);
+    if (rc) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (N > 0 && C > 0) {
+        const int npart = launch_amax_partials(dY, N * C, part, nullptr, st);
+        launch_amax_final(part, npart, amax, st);
+        QuantParams pr{}, pc{};
+        pr.rounding = pc.rounding = 1;
+        pr.scale_up = pc.scale_up = 1;
+        pr.amax_scalar = pc.amax_scalar = amax;
+        const uint64_t k3 = stream_key(seed, c[0].tensor_id), k5 = stream_key(seed, c[2].tensor_id);
+        pr.k0 = (uint32_t)k3; pr.k1 = (uint32_t)(k3 >> 32);
+        pc.k0 = (uint32_t)k5; pc.k1 = (uint32_t)(k5 >> 32);
+        QuantOut orow{q3.codes, q3.scales, q3.gscale, nullptr}, ocol{q5.codes, q5.scales, q5.gscale, nullptr};
+        if (launch_quant_dual_bf16(dY, N, C, pr, orow, pc, ocol, st) != hipSuccess) return NVFP4_ERR_HIP;
+    }
+    q3.rows = N; q3.K = C; q5.rows = C; q5.K = N;
+    rc = run_quantize(Wq_ctx, p4, &c[1], &q4, nullptr, st);
+    if (rc) return rc;
+    rc = run_gemm(&q3, &q4, dX, out_dtype, gws, gbytes, st);
+    if (rc) return rc;
+    rc = run_quantize(Xq_ctx, p6, &c[3], &q6, nullptr, st);
+    if (rc) return rc;
+    return run_gemm(&q5, &q6, dW, out_dtype, gws, gbytes, st);
 }
 
 }  // extern "C"

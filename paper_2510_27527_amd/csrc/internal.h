@@ -48,6 +48,10 @@ hipError_t launch_quant_row_bf16(const void *src, int64_t rows, int64_t K, const
 // column-wise quantization of a bf16 [R x C] array: output [C x R] grouped along R
 hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
                                  hipStream_t st);
+// both at once from one read of a bf16 [R x C] array: row-wise [R x C] (prow / orow) and column-wise [C x R]
+// (pcol / ocol); the two share rounding mode, scale rounding and the source of the tensor maximum
+hipError_t launch_quant_dual_bf16(const void *src, int64_t R, int64_t C, const QuantParams &prow, const QuantOut &orow,
+                                  const QuantParams &pcol, const QuantOut &ocol, hipStream_t st);
 // column-wise re-quantization of an NVFP4 [R x C] tensor: output [C x R] grouped along R
 hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
                               hipStream_t st);

@@ -213,6 +213,7 @@ struct ColArgs {
     const float *src_gscale;
     int64_t R, C;
     KArgs k;
+    KArgs krow;                // DUAL: the row-wise operand produced from the same read
 };
 
 // dword column of the tile, rotated by 4 per 16 rows
@@ -234,7 +235,9 @@ __device__ __forceinline__ void decode_group_bf16(uint2 codes, uint32_t sc, uint
     }
 }
 
-template <int ROUND, bool SUP, bool PACKED>
+// DUAL (bf16 source only): the tile's rows are also quantized row-wise (groups along C) while they pass through
+// registers on the way into LDS, so one read of the source yields both backward operands of dY (Q3 and Q5).
+template <int ROUND, bool SUP, bool PACKED, bool DUAL = false>
 __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint32_t tile[kTileR * 32];
@@ -242,8 +245,24 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
     __shared__ float red[4];
     const int tid = threadIdx.x;
     const int64_t R = a.R, C = a.C;
-    const int64_t R0 = (int64_t)blockIdx.y * kTileR, C0 = (int64_t)blockIdx.x * kTileC;
+    // Workgroup ids are dealt round-robin over the 8 XCDs.  A packed source has only 32 bytes of codes per row and
+    // tile, so there each XCD gets a contiguous run of tiles (column tile fastest): neighbouring column tiles,
+    // which share the source's cache lines, then meet in one L2.
+    const int64_t tiles_c = (C + kTileC - 1) / kTileC, total = tiles_c * ((R + kTileR - 1) / kTileR);
+    int64_t tid_x = blockIdx.x;
+    {
+        const int64_t per_xcd = total / 8;
+        if (PACKED && tid_x < per_xcd * 8) tid_x = (tid_x & 7) * per_xcd + (tid_x >> 3);
+    }
+    const bool first_tile = tid_x == 0;
+    const int64_t R0 = (tid_x / tiles_c) * kTileR, C0 = (tid_x % tiles_c) * kTileC;
     fill_inv_table(inv_tab);
+    const OuterScale os = outer_scale(block_tensor_amax(a.k, red));
+    if (first_tile && tid == 0) {
+        a.k.gscale[0] = os.S_g;
+        if (DUAL) a.krow.gscale[0] = os.S_g;
+    }
+    if (DUAL) __syncthreads();          // the reciprocal table is used in phase 1
 
     // phase 1: tile -> LDS as bf16 pairs, row-major with rotated columns
     if (!PACKED) {
@@ -251,9 +270,33 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
         for (int pass = 0; pass < 4; ++pass) {
             const int row = pass * 32 + (tid >> 3), q = tid & 7;
             const int64_t gr = R0 + row, gc = C0 + q * 8;
+            const bool valid = gr < R && gc < C;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (gr < R && gc < C) v = a.src[(gr * C + gc) >> 3];
+            if (valid) v = a.src[(gr * C + gc) >> 3];
             *reinterpret_cast<uint4 *>(&tile[tile_pos(row, q * 4)]) = v;
+            if (DUAL) {
+                // row-wise: lanes q, q^1 hold one group of 16 along C
+                const uint32_t hm = absmax8_bits(v);
+                const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
+                const uint32_t bm = hm > o1 ? hm : o1;
+                const uint32_t sc = e4m3_round<SUP>(u2f(bm << 16) * os.inv_cg);
+                const float r = os.inv_sg * inv_tab[sc];
+                const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                                    bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+                const int64_t e0 = gr * C + gc;
+                const uint32_t qd = quant8<ROUND>(x, r, (uint32_t)(e0 >> 1), a.krow.k0, a.krow.k1);
+                if (valid) a.krow.codes[e0 >> 3] = qd;
+                const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
+                const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
+                if (valid && q == 0) {
+                    if ((C & 63) == 0) {
+                        *reinterpret_cast<uint32_t *>(a.krow.scales + (e0 >> 4)) = s4;
+                    } else {
+                        for (int b = 0; b < 4; ++b)
+                            if (gc + 16 * b < C) a.krow.scales[(e0 >> 4) + b] = (uint8_t)(s4 >> (8 * b));
+                    }
+                }
+            }
         }
     } else {
         const int row = tid >> 1, half = tid & 1;
@@ -272,8 +315,6 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
             *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw + 4)]) = make_uint4(d[4], d[5], d[6], d[7]);
         }
     }
-    const OuterScale os = outer_scale(block_tensor_amax(a.k, red));
-    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) a.k.gscale[0] = os.S_g;
     const float src_sg = PACKED ? a.src_gscale[0] : 1.0f;
     __syncthreads();
 
@@ -344,7 +385,7 @@ void launch_row_t(const void *src, int64_t nchunks, const KArgs &k, bool deq, hi
 template <bool PACKED>
 void launch_col_t(const ColArgs &a, int rounding, int scale_up, hipStream_t st)
 {
-    dim3 grid((unsigned)((a.C + kTileC - 1) / kTileC), (unsigned)((a.R + kTileR - 1) / kTileR));
+    dim3 grid((unsigned)(((a.C + kTileC - 1) / kTileC) * ((a.R + kTileR - 1) / kTileR)));
     if (rounding == 0) {
         if (scale_up) hipLaunchKernelGGL((quant_col_kernel<0, true, PACKED>), grid, dim3(kThreads), 0, st, a);
         else          hipLaunchKernelGGL((quant_col_kernel<0, false, PACKED>), grid, dim3(kThreads), 0, st, a);
@@ -407,6 +448,27 @@ hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const Qu
     a.C = C;
     a.k = make_kargs(p, o);
     launch_col_t<false>(a, p.rounding, p.scale_up, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_quant_dual_bf16(const void *src, int64_t R, int64_t C, const QuantParams &prow, const QuantOut &orow,
+                                  const QuantParams &pcol, const QuantOut &ocol, hipStream_t st)
+{
+    if (R == 0 || C == 0) return hipSuccess;
+    ColArgs a{};
+    a.src = reinterpret_cast<const uint4 *>(src);
+    a.R = R;
+    a.C = C;
+    a.k = make_kargs(pcol, ocol);
+    a.krow = make_kargs(prow, orow);
+    dim3 grid((unsigned)(((C + kTileC - 1) / kTileC) * ((R + kTileR - 1) / kTileR)));
+    const int sel = (pcol.rounding << 1) | pcol.scale_up;
+    switch (sel) {
+        case 0: hipLaunchKernelGGL((quant_col_kernel<0, false, false, true>), grid, dim3(kThreads), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((quant_col_kernel<0, true, false, true>), grid, dim3(kThreads), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((quant_col_kernel<1, false, false, true>), grid, dim3(kThreads), 0, st, a); break;
+        default: hipLaunchKernelGGL((quant_col_kernel<1, true, false, true>), grid, dim3(kThreads), 0, st, a); break;
+    }
     return hipGetLastError();
 }
 

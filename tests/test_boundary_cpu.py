@@ -111,6 +111,19 @@ def test_gemm_and_linear_reject_bad_arguments(lib):
     assert dw(128, 128, 64, wsb=100) == -4
 
 
+def test_fused_backward_rejects_bad_arguments(lib):
+    X, W = _tensor(128, 128), _tensor(64, 128)
+    f = lambda N, D, Cc, x=X, w=W, wsb=1 << 40: lib.nvfp4_linear_bwd(FAKE, C.byref(x), C.byref(w), N, D, Cc, FAKE, FAKE, 0,
+                                                                  0, 0, FAKE, wsb, None)
+    assert f(128, 128, 32) == -2
+    assert f(96, 128, 64) == -2
+    assert f(128, 64, 64) == -6
+    assert f(128, 128, 64, wsb=64) == -4
+    assert lib.nvfp4_linear_bwd(None, C.byref(X), C.byref(W), 128, 128, 64, FAKE, FAKE, 0, 0, 0, FAKE, 1 << 40, None) == -1
+    assert lib.nvfp4_workspace_bytes(B.OP_LINEAR_BWD, 128, 128, 64, 0) >= \
+        lib.nvfp4_workspace_bytes(B.OP_LINEAR_BWD_DX, 128, 128, 64, 0)
+
+
 def test_workspace_sizes(lib):
     assert lib.nvfp4_workspace_bytes(99, 1, 1, 1, 0) == 0
     q = lib.nvfp4_workspace_bytes(B.OP_QUANTIZE, 8192, 8192, 0, 0)

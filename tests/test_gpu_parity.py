@@ -306,3 +306,20 @@ def test_same_seed_same_bytes_other_seed_other_bytes():
     torch.cuda.synchronize()
     assert torch.equal(a.codes, b.codes) and torch.equal(a.scales, b.scales)
     assert (a.codes != c.codes).float().mean().item() > 0.2
+
+
+@pytest.mark.parametrize("N,D,C", [(256, 512, 512), (192, 320, 448), (1088, 192, 576), (128, 64, 1088)])
+def test_fused_backward_equals_separate_calls(N, D, C):
+    """nvfp4_linear_bwd (one read of dY for both of its quantizations) gives the bytes of the two separate calls."""
+    Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed=21)
+    X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
+    for out_dtype in (1, 0):
+        _, Xq, Wq = tj.linear_fwd(X, W, out_dtype)
+        dX1 = tj.linear_bwd_dx(dY, Wq, 17, 3, out_dtype)
+        dW1 = tj.linear_bwd_dw(dY, Xq, 17, 3, out_dtype)
+        dX2, dW2 = tj.linear_bwd(dY, Xq, Wq, 17, 3, out_dtype)
+        torch.cuda.synchronize()
+        assert torch.equal(dX1, dX2) and torch.equal(dW1, dW2)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    ref, absref = oracle.gemm_nt(*oracle.linear_bwd_dw_operands(dYb, oXq, 17, 3))
+    check_product(dW2, ref, absref, "fused dW")
