@@ -85,13 +85,32 @@ __device__ __forceinline__ uint32_t e2m1_rtn(float y)
     return (hi + lo - 254u) | ((f2u(y) >> 28) & 8u);
 }
 
+// The same rounding for two values at once by the hardware's FP32 -> FP4 conversion, which lands in byte
+// SEL of `old`: first value in the low nibble.  (It agrees with e2m1_rtn on every binary32 pattern below
+// 16 in magnitude, both signs, -0 and subnormals included; nvfp4_selftest re-checks that on the device.)
+template <int SEL>
+__device__ __forceinline__ uint32_t e2m1_rtn_pair(uint32_t old, float y0, float y1)
+{
+    return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(old, y0, y1, 1.0f, SEL);
+}
+
 // Sec. 2.1 stochastic rounding of y with 16 uniform bits u: scaled by 2^-126 the value's
 // binary32 pattern is the E2M1 pattern extended by 22 fraction bits (fixed point below 1),
 // so adding u at bit 6 and truncating rounds up with probability floor(frac * 2^16) / 2^16.
+// CLAMP = false is for callers that know |y| <= 6 * (1 + 2^-17): such a y cannot carry into an
+// eighth code (upward-rounded block scales guarantee it).
+template <bool CLAMP>
 __device__ __forceinline__ uint32_t e2m1_sr(float y, uint32_t u16)
 {
-    float a = fminf(fabsf(y), 6.0f);
-    uint32_t w = f2u(a * 0x1p-126f) + (u16 << 6);
+    uint32_t tb;
+    if (CLAMP) {
+        uint32_t ab = f2u(y) & 0x7FFFFFFFu;            // |y| as an integer: ordered like the value
+        ab = ab < 0x40C00000u ? ab : 0x40C00000u;      // min(|y|, 6)
+        tb = f2u(u2f(ab) * 0x1p-126f);
+    } else {
+        tb = f2u(__builtin_fabsf(y) * 0x1p-126f);
+    }
+    const uint32_t w = tb + (u16 << 6);
     return (w >> 22) | ((f2u(y) >> 28) & 8u);
 }
 

@@ -7,6 +7,8 @@
 //                   both the 128-bit row writes and the per-column reads are conflict free), each
 //                   lane then owns two columns x 16 rows; the output is the transposed operand
 //   requant_col     same, the source being a packed NVFP4 tensor (Q4 / Q6)
+#include <type_traits>
+
 #include "device_fmt.h"
 #include "internal.h"
 
@@ -50,22 +52,24 @@ __device__ __forceinline__ void fill_inv_table(float *tab)
 }
 
 // eight consecutive elements of one group -> eight codes in one dword (element 0 in the low nibble)
-template <int ROUND>
+template <int ROUND, bool SUP>
 __device__ __forceinline__ uint32_t quant8(const float (&x)[8], float r, uint32_t pair0, uint32_t k0, uint32_t k1)
 {
     uint32_t out = 0;
+    if (ROUND == 0) {
+        out = e2m1_rtn_pair<0>(out, x[0] * r, x[1] * r);
+        out = e2m1_rtn_pair<1>(out, x[2] * r, x[3] * r);
+        out = e2m1_rtn_pair<2>(out, x[4] * r, x[5] * r);
+        out = e2m1_rtn_pair<3>(out, x[6] * r, x[7] * r);
+        return out;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        float y0 = x[2 * j] * r, y1 = x[2 * j + 1] * r;
-        uint32_t c0, c1;
-        if (ROUND == 0) {
-            c0 = e2m1_rtn(y0);
-            c1 = e2m1_rtn(y1);
-        } else {
-            uint32_t h = pair_bits(pair0 + j, k0, k1);
-            c0 = e2m1_sr(y0, h & 0xFFFFu);
-            c1 = e2m1_sr(y1, h >> 16);
-        }
+        const float y0 = x[2 * j] * r, y1 = x[2 * j + 1] * r;
+        const uint32_t h = pair_bits(pair0 + j, k0, k1);
+        // upward-rounded scales keep |y| <= 6 up to a few ulp, so no clamp is needed there
+        const uint32_t c0 = e2m1_sr<!SUP>(y0, h & 0xFFFFu);
+        const uint32_t c1 = e2m1_sr<!SUP>(y1, h >> 16);
         out |= (c0 | (c1 << 4)) << (8 * j);
     }
     return out;
@@ -134,6 +138,15 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
     __shared__ float inv_tab[128];
     __shared__ float red[4];
     const int tid = threadIdx.x;
+    // the workgroup's data first: these loads do not depend on the scale set-up below and overlap with it
+    const int64_t c0 = (int64_t)blockIdx.x * kRowIter * kThreads + tid;
+    const bool full = ((int64_t)blockIdx.x + 1) * kRowIter * kThreads <= nchunks;
+    uint4 vs[kRowIter];
+#pragma unroll
+    for (int it = 0; it < kRowIter; ++it) {
+        vs[it] = make_uint4(0, 0, 0, 0);
+        if (full || c0 + it * kThreads < nchunks) vs[it] = src[c0 + it * kThreads];
+    }
     fill_inv_table(inv_tab);
     OuterScale os;
     // Largest dequantized magnitude.  In tensor mode the group holding the tensor maximum always gets
@@ -151,50 +164,55 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
     }
     __syncthreads();
     float deq = 0.0f;
-#pragma unroll 2
-    for (int it = 0; it < kRowIter; ++it) {
-        const int64_t c = ((int64_t)blockIdx.x * kRowIter + it) * kThreads + tid;
-        const bool valid = c < nchunks;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (valid) v = src[c];
-        const uint32_t hm = absmax8_bits(v);
-        const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
-        const uint32_t bm = hm > o1 ? hm : o1;
-        if (OUTER == 1) {
-            uint32_t gm = bm, t;
-            t = dpp<DPP_QUAD_XOR2>(gm);       gm = gm > t ? gm : t;
-            t = dpp<DPP_ROW_HALF_MIRROR>(gm); gm = gm > t ? gm : t;
-            t = dpp<DPP_ROW_MIRROR>(gm);      gm = gm > t ? gm : t;
-            os = outer_scale(u2f(gm << 16));
-            if (valid && (tid & 15) == 0) a.gscale[c >> 4] = os.S_g;
-        }
-        const float amax_b = u2f(bm << 16);
-        const float s = amax_b * os.inv_cg;
-        const uint32_t sc = e4m3_round<SUP>(s);
-        const float r = os.inv_sg * inv_tab[sc];
-        const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
-                            bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-        const uint32_t q = quant8<ROUND>(x, r, (uint32_t)(c * 4), a.k0, a.k1);
-        if (valid) a.codes[c] = q;
-        // four scale bytes (lanes c, c+2, c+4, c+6) travel to the lane with c % 8 == 0
-        const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
-        const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
-        if (valid && (tid & 7) == 0) {
-            if (c + 8 <= nchunks) {
-                reinterpret_cast<uint32_t *>(a.scales)[c >> 3] = s4;
-            } else {
-                for (int b = 0; b < 4; ++b)
-                    if (c + 2 * b < nchunks) a.scales[(c >> 1) + b] = (uint8_t)(s4 >> (8 * b));
+    // CHECK = false: every chunk of this workgroup exists (all but the last workgroup), no predication
+    auto run = [&](auto chk) {
+        constexpr bool CHECK = decltype(chk)::value;
+#pragma unroll
+        for (int it = 0; it < kRowIter; ++it) {
+            const int64_t c = c0 + it * kThreads;
+            const bool valid = !CHECK || c < nchunks;
+            const uint4 v = vs[it];
+            const uint32_t hm = absmax8_bits(v);
+            const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
+            const uint32_t bm = hm > o1 ? hm : o1;
+            if (OUTER == 1) {
+                uint32_t gm = bm, t;
+                t = dpp<DPP_QUAD_XOR2>(gm);       gm = gm > t ? gm : t;
+                t = dpp<DPP_ROW_HALF_MIRROR>(gm); gm = gm > t ? gm : t;
+                t = dpp<DPP_ROW_MIRROR>(gm);      gm = gm > t ? gm : t;
+                os = outer_scale(u2f(gm << 16));
+                if (valid && (tid & 15) == 0) a.gscale[c >> 4] = os.S_g;
+            }
+            const float amax_b = u2f(bm << 16);
+            const float s = amax_b * os.inv_cg;
+            const uint32_t sc = e4m3_round<SUP>(s);
+            const float r = os.inv_sg * inv_tab[sc];
+            const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                                bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+            const uint32_t q = quant8<ROUND, SUP>(x, r, (uint32_t)(c * 4), a.k0, a.k1);
+            if (valid) a.codes[c] = q;
+            // four scale bytes (lanes c, c+2, c+4, c+6) travel to the lane with c % 8 == 0
+            const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
+            const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
+            if (valid && (tid & 7) == 0) {
+                if (!CHECK || c + 8 <= nchunks) {
+                    reinterpret_cast<uint32_t *>(a.scales)[c >> 3] = s4;
+                } else {
+                    for (int b = 0; b < 4; ++b)
+                        if (c + 2 * b < nchunks) a.scales[(c >> 1) + b] = (uint8_t)(s4 >> (8 * b));
+                }
+            }
+            if (DEQ && reduce_deq) {
+                // the group's largest element gets the group's largest code (rounding is monotone)
+                const uint32_t mm = e2m1_rtn(amax_b * r) & 7u;
+                float val = e2m1_value(mm) * e4m3_value(sc);
+                if (OUTER == 1) val = val * os.S_g;
+                deq = fmaxf(deq, val);
             }
         }
-        if (DEQ && reduce_deq) {
-            // the group's largest element gets the group's largest code (rounding is monotone)
-            const uint32_t mm = e2m1_rtn(amax_b * r) & 7u;
-            float val = e2m1_value(mm) * e4m3_value(sc);
-            if (OUTER == 1) val = val * os.S_g;
-            deq = fmaxf(deq, val);
-        }
-    }
+    };
+    if (full) run(std::false_type{});
+    else run(std::true_type{});
     if (DEQ && reduce_deq) {
         if (OUTER == 0) deq = deq * os.S_g;
         publish_deq_max(deq, a.amax_deq, red);
@@ -256,6 +274,16 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
     }
     const bool first_tile = tid_x == 0;
     const int64_t R0 = (tid_x / tiles_c) * kTileR, C0 = (tid_x % tiles_c) * kTileC;
+    // the tile's data first: these loads do not depend on the scale set-up and overlap with it
+    uint4 vs[4];
+    if (!PACKED) {
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int64_t gr = R0 + pass * 32 + (tid >> 3), gc = C0 + (tid & 7) * 8;
+            vs[pass] = make_uint4(0, 0, 0, 0);
+            if (gr < R && gc < C) vs[pass] = a.src[(gr * C + gc) >> 3];
+        }
+    }
     fill_inv_table(inv_tab);
     const OuterScale os = outer_scale(block_tensor_amax(a.k, red));
     if (first_tile && tid == 0) {
@@ -271,8 +299,7 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
             const int row = pass * 32 + (tid >> 3), q = tid & 7;
             const int64_t gr = R0 + row, gc = C0 + q * 8;
             const bool valid = gr < R && gc < C;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (valid) v = a.src[(gr * C + gc) >> 3];
+            const uint4 v = vs[pass];
             *reinterpret_cast<uint4 *>(&tile[tile_pos(row, q * 4)]) = v;
             if (DUAL) {
                 // row-wise: lanes q, q^1 hold one group of 16 along C
@@ -284,7 +311,7 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
                 const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
                                     bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
                 const int64_t e0 = gr * C + gc;
-                const uint32_t qd = quant8<ROUND>(x, r, (uint32_t)(e0 >> 1), a.krow.k0, a.krow.k1);
+                const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 1), a.krow.k0, a.krow.k1);
                 if (valid) a.krow.codes[e0 >> 3] = qd;
                 const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
                 const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
@@ -347,8 +374,8 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
         }
         const uint32_t pair0 = (uint32_t)((c * R + k_first) >> 1);
         uint2 q;
-        q.x = quant8<ROUND>(x0, r, pair0, a.k.k0, a.k.k1);
-        q.y = quant8<ROUND>(x1, r, pair0 + 4, a.k.k0, a.k.k1);
+        q.x = quant8<ROUND, SUP>(x0, r, pair0, a.k.k0, a.k.k1);
+        q.y = quant8<ROUND, SUP>(x1, r, pair0 + 4, a.k.k0, a.k.k1);
         *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(a.k.codes) + ((c * R + k_first) >> 1)) = q;
         a.k.scales[(c * R + k_first) >> 4] = (uint8_t)sc;
     }
