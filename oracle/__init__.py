@@ -49,10 +49,12 @@ def lib():
         L.oracle_e4m3_round.argtypes = [f32, i32]
         L.oracle_stream_key.restype = u64
         L.oracle_stream_key.argtypes = [u64, u32]
-        L.oracle_pair_bits.restype = u32
-        L.oracle_pair_bits.argtypes = [u32, u64]
-        L.oracle_rand16.restype = u32
-        L.oracle_rand16.argtypes = [u64, u64]
+        L.oracle_quad_bits.restype = u32
+        L.oracle_quad_bits.argtypes = [u32, u64]
+        L.oracle_rand22.restype = u32
+        L.oracle_rand22.argtypes = [u64, u64]
+        L.oracle_round_sr_count_up.restype = i64
+        L.oracle_round_sr_count_up.argtypes = [f32, C.POINTER(C.c_int)]
         L.oracle_round_rtn.restype = i32
         L.oracle_round_rtn.argtypes = [f32]
         L.oracle_round_sr.restype = i32

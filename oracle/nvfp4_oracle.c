@@ -32,13 +32,18 @@
  *       the block maximum and bias the estimate).
  *   R4  Deterministic rounding breaks ties toward the even code.
  *   R5  Stochastic rounding: the paper's xi ~ U(-D/2, D/2) with D = q2 - q1 and
- *       "x + xi <= midpoint -> q1" is taken on a discrete uniform of 16 bits:
- *       with f = (a - q1)/D and L = floor(f * 2^16), a is rounded up iff
- *       u + L >= 2^16 for u uniform on {0..65535}; so P(q2) = L / 2^16.  Below
- *       1 (the E2M1 subnormal range) a is first rounded to a multiple of 2^-23.
- *   R6  The random 16 bits of output element e (index in the quantized
- *       operand's own [rows x K] view) come from a counter-based hash of the
- *       pair index e>>1, keyed by (seed, tensor id); see rand16() below.
+ *       "x + xi <= midpoint -> q1" is taken on a discrete uniform of 22 bits:
+ *       with f = (a - q1)/D and L = floor(f * 2^22), a is rounded up iff
+ *       u + L >= 2^22 for u uniform on {0..2^22-1}; so P(q2) = L / 2^22.  Below
+ *       1 (the E2M1 subnormal range) a is first rounded to a multiple of 2^-23,
+ *       which makes f * 2^22 an integer there; from 1 to 6 a binary32 value has
+ *       at most 22 bits below the E2M1 mantissa bit, so L = f * 2^22 exactly and
+ *       the rounding is exactly unbiased on that image of a.
+ *   R6  The 22 random bits of output element e (index in the quantized
+ *       operand's own [rows x K] view) come from a counter-based 32-bit hash h of
+ *       the quad index e>>2, keyed by (seed, tensor id): element i = e&3 of the
+ *       quad takes the top 22 bits of h rotated right by 8*i bits, so each
+ *       element's leading byte is a byte of h of its own; see rand22() below.
  *   R7  A code is sign<<3 | index into the ascending value set, the sign bit
  *       being the input's sign bit (so -0 codes occur and decode to -0).
  *       Element k of a row sits in byte k/2, even k in the low nibble.
@@ -114,8 +119,8 @@ uint64_t oracle_stream_key(uint64_t seed, uint32_t tensor_id)
     return mix64(a ^ b);
 }
 
-/* R6: 32 random bits of pair p under key (k0 = low word, k1 = high word) */
-uint32_t oracle_pair_bits(uint32_t p, uint64_t key)
+/* R6: 32 random bits of quad p under key (k0 = low word, k1 = high word) */
+uint32_t oracle_quad_bits(uint32_t p, uint64_t key)
 {
     uint32_t k0 = (uint32_t)key, k1 = (uint32_t)(key >> 32);
     uint32_t h = p + k0;
@@ -125,11 +130,13 @@ uint32_t oracle_pair_bits(uint32_t p, uint64_t key)
     return h;
 }
 
-/* R6: 16 random bits of element e */
-uint32_t oracle_rand16(uint64_t e, uint64_t key)
+/* R6: 22 random bits of element e */
+uint32_t oracle_rand22(uint64_t e, uint64_t key)
 {
-    uint32_t h = oracle_pair_bits((uint32_t)(e >> 1), key);
-    return (e & 1) ? (h >> 16) : (h & 0xFFFFu);
+    uint32_t h = oracle_quad_bits((uint32_t)(e >> 2), key);
+    unsigned i = (unsigned)(e & 3);
+    uint32_t w = i ? (h >> (8 * i)) | (h << (32 - 8 * i)) : h;   /* rotate right by 8 i */
+    return w >> 10;                                              /* its top 22 bits */
 }
 
 /* -------------------------------------------------------------- rounding -- */
@@ -146,8 +153,8 @@ int oracle_round_rtn(float a)
     return best;
 }
 
-/* Sec. 2.1 round_{FP4,S} with the discrete uniform of R5; u16 in [0, 65536) */
-int oracle_round_sr(float a, uint32_t u16)
+/* Sec. 2.1 round_{FP4,S} with the discrete uniform of R5; u22 in [0, 2^22) */
+int oracle_round_sr(float a, uint32_t u22)
 {
     if (a < 1.0f) a = rintf(a * 8388608.0f) * (1.0f / 8388608.0f);   /* R5: 2^-23 grid below 1 */
     if (a >= 6.0f) return 7;
@@ -156,8 +163,24 @@ int oracle_round_sr(float a, uint32_t u16)
         if (FP4_VALUES[i] <= a) i1 = i;                               /* q1 <= a < q2 */
     float q1 = FP4_VALUES[i1], q2 = FP4_VALUES[i1 + 1];
     double f = ((double)a - (double)q1) / ((double)q2 - (double)q1);
-    uint32_t L = (uint32_t)floor(f * 65536.0);
-    return (u16 + L >= 65536u) ? i1 + 1 : i1;
+    uint32_t L = (uint32_t)floor(f * 4194304.0);
+    return (u22 + L >= 4194304u) ? i1 + 1 : i1;
+}
+
+/* test helper: over all 2^22 values of u, how often a is rounded up (returns -1 if the rounded-up set is not
+ * the upper interval of u, or a result other than the two neighbours appears) */
+int64_t oracle_round_sr_count_up(float a, int *lower_index)
+{
+    int base = oracle_round_sr(a, 0);
+    int64_t ups = 0;
+    int seen_up = 0;
+    for (uint32_t u = 0; u < 4194304u; ++u) {
+        int m = oracle_round_sr(a, u);
+        if (m == base + 1) { seen_up = 1; ++ups; }
+        else if (m != base || seen_up) return -1;
+    }
+    *lower_index = base;
+    return ups;
 }
 
 /* ------------------------------------------------------------- quantizer -- */
@@ -196,7 +219,7 @@ int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
     if (rounding != ROUND_RTN && rounding != ROUND_SR) return -1;
     if (scale_round == SCALE_DEFAULT) scale_round = rounding == ROUND_RTN ? SCALE_NE : SCALE_UP;
     if (scale_round != SCALE_NE && scale_round != SCALE_UP) return -1;
-    if ((double)rows * (double)K > 8589934592.0) return -1;        /* pair index must fit 32 bits */
+    if ((double)rows * (double)K > 17179869184.0) return -1;       /* quad index must fit 32 bits */
 
     const uint64_t key = oracle_stream_key(seed, tensor_id);
     const int64_t outer_len = outer_mode == OUTER_TENSOR ? K : 128;
@@ -238,7 +261,7 @@ int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
                     float a = fabsf(y); if (a > 6.0f) a = 6.0f;
                     int m;
                     if (rounding == ROUND_RTN) m = oracle_round_rtn(a);
-                    else m = oracle_round_sr(a, oracle_rand16((uint64_t)(r * K + k), key));
+                    else m = oracle_round_sr(a, oracle_rand22((uint64_t)(r * K + k), key));
                     int neg = signbit(xb[i]) != 0;
                     uint8_t nib = (uint8_t)((neg << 3) | m);
                     uint8_t *byte = codes + r * (K / 2) + k / 2;

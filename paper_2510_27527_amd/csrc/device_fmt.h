@@ -87,38 +87,50 @@ __device__ __forceinline__ uint32_t e2m1_rtn(float y)
 
 // The same rounding for two values at once by the hardware's FP32 -> FP4 conversion, which lands in byte
 // SEL of `old`: first value in the low nibble.  (It agrees with e2m1_rtn on every binary32 pattern below
-// 16 in magnitude, both signs, -0 and subnormals included; nvfp4_selftest re-checks that on the device.)
+// 16 in magnitude, both signs, -0 and subnormals included.)
 template <int SEL>
 __device__ __forceinline__ uint32_t e2m1_rtn_pair(uint32_t old, float y0, float y1)
 {
     return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(old, y0, y1, 1.0f, SEL);
 }
 
-// Sec. 2.1 stochastic rounding of y with 16 uniform bits u: scaled by 2^-126 the value's
-// binary32 pattern is the E2M1 pattern extended by 22 fraction bits (fixed point below 1),
-// so adding u at bit 6 and truncating rounds up with probability floor(frac * 2^16) / 2^16.
-// CLAMP = false is for callers that know |y| <= 6 * (1 + 2^-17): such a y cannot carry into an
-// eighth code (upward-rounded block scales guarantee it).
-template <bool CLAMP>
-__device__ __forceinline__ uint32_t e2m1_sr(float y, uint32_t u16)
+// Sec. 2.1 stochastic rounding of two values by the hardware's FP32 -> FP4 conversion with a random word.  Scaled
+// by 2^-126 a magnitude's binary32 pattern is its E2M1 pattern extended by 22 fraction bits (fixed point below 1,
+// where the denormalisation rounds to a multiple of 2^-23 of the value); the conversion adds 22 random bits to that
+// fraction, truncates and saturates at 6, so a value moves to its upper neighbour with probability frac exactly.
+// The first value takes bits 31..10 of the random word, the second bits 30..9: the two draws of one conversion
+// share all but one bit, so a caller that wants independent draws converts twice and keeps one nibble of each.
+//
+// e2m1_sr8 rounds eight values: the even ones with the words h[j], the odd ones with the words g[j]; element 0 lands
+// in the low nibble.  Written as one block of instructions because the conversion keeps the other three bytes of its
+// destination, which the compiler's builtin for it does not model (it lets later conversions land in other
+// registers); the two destination chains alternate so that no conversion follows the one it depends on directly,
+// and the closing idle cycle covers the partial-register write before the first reader.
+__device__ __forceinline__ uint32_t e2m1_sr8(float y0, float y1, float y2, float y3, float y4, float y5, float y6,
+                                             float y7, const uint32_t (&h)[4], const uint32_t (&g)[4])
 {
-    uint32_t tb;
-    if (CLAMP) {
-        uint32_t ab = f2u(y) & 0x7FFFFFFFu;            // |y| as an integer: ordered like the value
-        ab = ab < 0x40C00000u ? ab : 0x40C00000u;      // min(|y|, 6)
-        tb = f2u(u2f(ab) * 0x1p-126f);
-    } else {
-        tb = f2u(__builtin_fabsf(y) * 0x1p-126f);
-    }
-    const uint32_t w = tb + (u16 << 6);
-    return (w >> 22) | ((f2u(y) >> 28) & 8u);
+    const float2_t p0 = {y0, y1}, p1 = {y2, y3}, p2 = {y4, y5}, p3 = {y6, y7};
+    uint32_t lo, hi;
+    asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %2, %6, 1.0\n\t"
+        "v_cvt_scalef32_sr_pk_fp4_f32 %1, %2, %10, 1.0\n\t"
+        "v_cvt_scalef32_sr_pk_fp4_f32 %0, %3, %7, 1.0 op_sel:[0,0,1,0]\n\t"
+        "v_cvt_scalef32_sr_pk_fp4_f32 %1, %3, %11, 1.0 op_sel:[0,0,1,0]\n\t"
+        "v_cvt_scalef32_sr_pk_fp4_f32 %0, %4, %8, 1.0 op_sel:[0,0,0,1]\n\t"
+        "v_cvt_scalef32_sr_pk_fp4_f32 %1, %4, %12, 1.0 op_sel:[0,0,0,1]\n\t"
+        "v_cvt_scalef32_sr_pk_fp4_f32 %0, %5, %9, 1.0 op_sel:[0,0,1,1]\n\t"
+        "v_cvt_scalef32_sr_pk_fp4_f32 %1, %5, %13, 1.0 op_sel:[0,0,1,1]\n\t"
+        "s_nop 0"
+        : "=&v"(lo), "=&v"(hi)
+        : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(h[0]), "v"(h[1]), "v"(h[2]), "v"(h[3]), "v"(g[0]), "v"(g[1]),
+          "v"(g[2]), "v"(g[3]));
+    return (lo & 0x0F0F0F0Fu) | (hi & 0xF0F0F0F0u);
 }
 
 // ---- stochastic-rounding bit generator --------------------------------------------------------
 
-// 32 bits for the element pair p of a stream keyed by (k0, k1): two rounds of
-// xorshift-multiply with the second key word folded in between
-__device__ __forceinline__ uint32_t pair_bits(uint32_t p, uint32_t k0, uint32_t k1)
+// 32 bits for the element quad p (four consecutive elements of the quantized operand) of a stream
+// keyed by (k0, k1): two rounds of xorshift-multiply with the second key word folded in between
+__device__ __forceinline__ uint32_t quad_bits(uint32_t p, uint32_t k0, uint32_t k1)
 {
     uint32_t h = p + k0;
     h ^= h >> 16;

@@ -17,7 +17,33 @@ namespace tj {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowIter = 8;    // 128-bit chunks per thread in the row kernel
+#ifndef TJ_ROW_ITER
+#define TJ_ROW_ITER 4
+#endif
+constexpr int kRowIter = TJ_ROW_ITER;    // 128-bit chunks per thread in the row kernel
+
+// 128-bit load of source data that this kernel reads exactly once (streaming hint: the line need not stay cached)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_stream(const uint4 *p)
+{
+#ifndef TJ_NO_NT_LD
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+#else
+    return *p;
+#endif
+}
+#ifdef TJ_NT_ST
+__device__ __forceinline__ void st_stream(uint32_t *p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+#else
+__device__ __forceinline__ void st_stream(uint32_t *p, uint32_t v) { *p = v; }
+#endif
+
+#ifdef TJ_COL_NT_LD
+__device__ __forceinline__ uint4 ld_col(const uint4 *p) { return ld_stream(p); }
+#else
+__device__ __forceinline__ uint4 ld_col(const uint4 *p) { return *p; }
+#endif
 
 struct KArgs {
     uint32_t *codes;
@@ -53,7 +79,7 @@ __device__ __forceinline__ void fill_inv_table(float *tab)
 
 // eight consecutive elements of one group -> eight codes in one dword (element 0 in the low nibble)
 template <int ROUND, bool SUP>
-__device__ __forceinline__ uint32_t quant8(const float (&x)[8], float r, uint32_t pair0, uint32_t k0, uint32_t k1)
+__device__ __forceinline__ uint32_t quant8(const float (&x)[8], float r, uint32_t quad0, uint32_t k0, uint32_t k1)
 {
     uint32_t out = 0;
     if (ROUND == 0) {
@@ -63,16 +89,16 @@ __device__ __forceinline__ uint32_t quant8(const float (&x)[8], float r, uint32_
         out = e2m1_rtn_pair<3>(out, x[6] * r, x[7] * r);
         return out;
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float y0 = x[2 * j] * r, y1 = x[2 * j + 1] * r;
-        const uint32_t h = pair_bits(pair0 + j, k0, k1);
-        // upward-rounded scales keep |y| <= 6 up to a few ulp, so no clamp is needed there
-        const uint32_t c0 = e2m1_sr<!SUP>(y0, h & 0xFFFFu);
-        const uint32_t c1 = e2m1_sr<!SUP>(y1, h >> 16);
-        out |= (c0 | (c1 << 4)) << (8 * j);
-    }
-    return out;
+    // One 32-bit hash per four elements; element i of the quad is rounded with the top 22 bits of the hash rotated
+    // right by 8 i, so its leading byte is a byte of its own.  The conversion looks at bits 31..10 of the word for
+    // its first value and at bits 30..9 for its second, hence the rotation by one more bit for odd elements; two
+    // conversions per pair, the first supplying the low nibbles, the second the high nibbles.  The conversion
+    // saturates at 6 by itself.
+    const uint32_t ha = quad_bits(quad0, k0, k1), hb = quad_bits(quad0 + 1, k0, k1);
+    const uint32_t h[4] = {ha, __builtin_amdgcn_alignbit(ha, ha, 16), hb, __builtin_amdgcn_alignbit(hb, hb, 16)};
+    const uint32_t g[4] = {__builtin_amdgcn_alignbit(ha, ha, 9), __builtin_amdgcn_alignbit(ha, ha, 25),
+                           __builtin_amdgcn_alignbit(hb, hb, 9), __builtin_amdgcn_alignbit(hb, hb, 25)};
+    return e2m1_sr8(x[0] * r, x[1] * r, x[2] * r, x[3] * r, x[4] * r, x[5] * r, x[6] * r, x[7] * r, h, g);
 }
 
 // workgroup maximum -> one atomic, and only if it can still raise the published value (the
@@ -145,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
 #pragma unroll
     for (int it = 0; it < kRowIter; ++it) {
         vs[it] = make_uint4(0, 0, 0, 0);
-        if (full || c0 + it * kThreads < nchunks) vs[it] = src[c0 + it * kThreads];
+        if (full || c0 + it * kThreads < nchunks) vs[it] = ld_stream(src + c0 + it * kThreads);
     }
     fill_inv_table(inv_tab);
     OuterScale os;
@@ -189,14 +215,14 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
             const float r = os.inv_sg * inv_tab[sc];
             const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
                                 bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-            const uint32_t q = quant8<ROUND, SUP>(x, r, (uint32_t)(c * 4), a.k0, a.k1);
-            if (valid) a.codes[c] = q;
+            const uint32_t q = quant8<ROUND, SUP>(x, r, (uint32_t)(c * 2), a.k0, a.k1);
+            if (valid) st_stream(a.codes + c, q);
             // four scale bytes (lanes c, c+2, c+4, c+6) travel to the lane with c % 8 == 0
             const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
             const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
             if (valid && (tid & 7) == 0) {
                 if (!CHECK || c + 8 <= nchunks) {
-                    reinterpret_cast<uint32_t *>(a.scales)[c >> 3] = s4;
+                    st_stream(reinterpret_cast<uint32_t *>(a.scales) + (c >> 3), s4);
                 } else {
                     for (int b = 0; b < 4; ++b)
                         if (c + 2 * b < nchunks) a.scales[(c >> 1) + b] = (uint8_t)(s4 >> (8 * b));
@@ -281,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
         for (int pass = 0; pass < 4; ++pass) {
             const int64_t gr = R0 + pass * 32 + (tid >> 3), gc = C0 + (tid & 7) * 8;
             vs[pass] = make_uint4(0, 0, 0, 0);
-            if (gr < R && gc < C) vs[pass] = a.src[(gr * C + gc) >> 3];
+            if (gr < R && gc < C) vs[pass] = ld_col(a.src + ((gr * C + gc) >> 3));
         }
     }
     fill_inv_table(inv_tab);
@@ -311,7 +337,7 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
                 const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
                                     bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
                 const int64_t e0 = gr * C + gc;
-                const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 1), a.krow.k0, a.krow.k1);
+                const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 2), a.krow.k0, a.krow.k1);
                 if (valid) a.krow.codes[e0 >> 3] = qd;
                 const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
                 const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
@@ -372,10 +398,10 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
             x1[i] = j == 0 ? bf16_lo(w[8 + i]) : bf16_hi(w[8 + i]);
             if (PACKED) { x0[i] = x0[i] * src_sg; x1[i] = x1[i] * src_sg; }
         }
-        const uint32_t pair0 = (uint32_t)((c * R + k_first) >> 1);
+        const uint32_t quad0 = (uint32_t)((c * R + k_first) >> 2);
         uint2 q;
-        q.x = quant8<ROUND, SUP>(x0, r, pair0, a.k.k0, a.k.k1);
-        q.y = quant8<ROUND, SUP>(x1, r, pair0 + 4, a.k.k0, a.k.k1);
+        q.x = quant8<ROUND, SUP>(x0, r, quad0, a.k.k0, a.k.k1);
+        q.y = quant8<ROUND, SUP>(x1, r, quad0 + 2, a.k.k0, a.k.k1);
         *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(a.k.codes) + ((c * R + k_first) >> 1)) = q;
         a.k.scales[(c * R + k_first) >> 4] = (uint8_t)sc;
     }

@@ -117,67 +117,81 @@ def test_rtn_is_argmin_with_even_ties():
         assert L.oracle_round_rtn(float(above)) == i + 1
 
 
-@pytest.mark.parametrize("a", [0.0, 0.1, 0.25, 0.49, 0.5, 0.77, 1.0, 1.3, 1.99, 2.0, 2.6, 3.999, 4.5, 5.9, 6.0])
+@pytest.mark.parametrize("a", [0.0, 0.1, 0.25, 0.49, 0.5, 0.77, 1.0, 1.3, 1.99, 2.0, 2.6, 3.999, 4.5, 5.9, 6.0,
+                               0.3000001, 1.0000001, 5.9999995])
 def test_sr_closed_form_probability(a):
-    """P(q2) = (x - q1)/(q2 - q1) (Sec. 2.1), here on a 16-bit uniform: exhaustive over all u."""
+    """P(q2) = (x - q1)/(q2 - q1) (Sec. 2.1), here on a 22-bit uniform: exhaustive over all 2^22 values of u."""
+    import ctypes
     L = oracle.lib()
     a32 = float(np.float32(a))
-    res = np.array([L.oracle_round_sr(a32, u) for u in range(0, 65536)])
-    i1 = int(np.searchsorted(GRID, a32, side="right") - 1)
+    lower = ctypes.c_int(0)
+    ups = L.oracle_round_sr_count_up(a32, ctypes.byref(lower))
+    assert ups >= 0                                       # only the two neighbours, rounded-up set = upper interval of u
     if a32 >= 6.0:
-        assert np.all(res == 7)
+        assert lower.value == 7 and ups == 0
         return
+    a_img = float(np.rint(np.float64(a32) * 2.0 ** 23) / 2.0 ** 23) if a32 < 1.0 else a32   # R5: 2^-23 grid below 1
+    i1 = int(np.searchsorted(GRID, a_img, side="right") - 1)
+    assert lower.value == i1
     q1, q2 = GRID[i1], GRID[i1 + 1]
-    assert set(np.unique(res)) <= {i1, i1 + 1}
-    p_up = np.mean(res == i1 + 1)
-    assert abs(p_up - (a32 - q1) / (q2 - q1)) <= 2.0 ** -16
+    assert ups == (a_img - q1) / (q2 - q1) * 2.0 ** 22       # exact: the closed form at 22-bit resolution
+    assert abs(ups / 2.0 ** 22 - (a32 - q1) / (q2 - q1)) <= 2.0 ** -21
     if a32 == q1:
-        assert p_up == 0.0                               # grid points never move
-    # the rounded-up set is an upper interval of u: u + L >= 2^16
-    ups = np.nonzero(res == i1 + 1)[0]
-    if len(ups):
-        assert ups.min() + len(ups) == 65536
+        assert ups == 0                                   # grid points never move
 
 
 def test_sr_mean_equals_value_on_average_over_u():
-    """E_u[round_S(a)] = a up to the 2^-16 probability resolution (unbiasedness, Sec. 2.1)."""
+    """E_u[round_S(a)] = a (unbiasedness, Sec. 2.1): mean over a stride of u values."""
     L = oracle.lib()
     rng = np.random.default_rng(4)
-    us = np.arange(0, 65536, 7)
-    for a in rng.uniform(0, 6, 40).astype(np.float32):
+    us = np.arange(0, 1 << 22, 977)
+    for a in rng.uniform(0, 6, 30).astype(np.float32):
         vals = np.array([GRID[L.oracle_round_sr(float(a), int(u))] for u in us])
-        step = 2.0
-        assert abs(vals.mean() - float(a)) < step * (7.0 / 65536 + 2.0 ** -15)
+        assert abs(vals.mean() - float(a)) < 2.0 * (977.0 / 2 ** 22 + 2.0 ** -21)
 
 
-def test_rand16_uniform_and_keyed():
+def test_rand22_uniform_and_keyed():
     L = oracle.lib()
     key = L.oracle_stream_key(7, 3)
     n = 1 << 16
-    u = np.array([L.oracle_rand16(e, key) for e in range(n)])
-    assert u.min() >= 0 and u.max() < 65536
+    u = np.array([L.oracle_rand22(e, key) for e in range(n)])
+    assert u.min() >= 0 and u.max() < (1 << 22)
     # chi-square on 256 buckets of the top byte, 255 dof: mean 255, sd ~22.6
-    counts = np.bincount(u >> 8, minlength=256)
+    counts = np.bincount(u >> 14, minlength=256)
     chi2 = ((counts - n / 256) ** 2 / (n / 256)).sum()
     assert chi2 < 255 + 6 * 22.6
-    # halves of a pair are different draws, neighbours are uncorrelated
-    assert abs(np.corrcoef(u[0::2], u[1::2])[0, 1]) < 0.02
-    assert abs(np.corrcoef(u[:-2], u[2:])[0, 1]) < 0.02
+    # low bits are uniform too
+    counts = np.bincount(u & 255, minlength=256)
+    assert ((counts - n / 256) ** 2 / (n / 256)).sum() < 255 + 6 * 22.6
+    # the four elements of a quad are different draws: every pair of positions is uncorrelated, also in the joint
+    # distribution of their leading bits (16 x 16 contingency table, 225 dof); so are neighbouring quads
+    for i in range(4):
+        for j in range(i + 1, 4):
+            assert abs(np.corrcoef(u[i::4], u[j::4])[0, 1]) < 0.03, (i, j)
+            table = np.zeros((16, 16))
+            np.add.at(table, (u[i::4] >> 18, u[j::4] >> 18), 1)
+            exp = table.sum() / 256
+            assert ((table - exp) ** 2 / exp).sum() < 225 + 6 * np.sqrt(2 * 225), (i, j)
+    assert abs(np.corrcoef(u[:-4], u[4:])[0, 1]) < 0.02
+    # the leading bytes of a quad's four draws are the four bytes of one hash word
+    for q in range(0, 64):
+        h = L.oracle_quad_bits(q, key)
+        assert [int(u[4 * q + i]) >> 14 for i in range(4)] == [(h >> 24) & 255, h & 255, (h >> 8) & 255, (h >> 16) & 255]
     # another tensor id or seed gives another stream
     for other in (L.oracle_stream_key(7, 4), L.oracle_stream_key(8, 3)):
-        v = np.array([L.oracle_rand16(e, other) for e in range(4096)])
+        v = np.array([L.oracle_rand22(e, other) for e in range(4096)])
         assert np.mean(v == u[:4096]) < 0.01
         assert abs(np.corrcoef(v, u[:4096])[0, 1]) < 0.06
 
 
-def test_pair_bits_avalanche():
+def test_quad_bits_avalanche():
     """Flipping one counter bit flips about half of the output bits."""
     L = oracle.lib()
     key = L.oracle_stream_key(0, 0)
     rng = np.random.default_rng(5)
     ps = rng.integers(0, 1 << 32, 400, dtype=np.uint64)
     for bit in range(32):
-        flips = [bin(L.oracle_pair_bits(int(p), key) ^ L.oracle_pair_bits(int(p) ^ (1 << bit), key)).count("1")
+        flips = [bin(L.oracle_quad_bits(int(p), key) ^ L.oracle_quad_bits(int(p) ^ (1 << bit), key)).count("1")
                  for p in ps]
         assert 13.0 < np.mean(flips) < 19.0, (bit, np.mean(flips))
 
