@@ -39,12 +39,6 @@ __device__ __forceinline__ void st_stream(uint32_t *p, uint32_t v) { __builtin_n
 __device__ __forceinline__ void st_stream(uint32_t *p, uint32_t v) { *p = v; }
 #endif
 
-#ifdef TJ_COL_NT_LD
-__device__ __forceinline__ uint4 ld_col(const uint4 *p) { return ld_stream(p); }
-#else
-__device__ __forceinline__ uint4 ld_col(const uint4 *p) { return *p; }
-#endif
-
 struct KArgs {
     uint32_t *codes;
     uint8_t *scales;
@@ -256,6 +250,7 @@ struct ColArgs {
     const uint8_t *src_scales;
     const float *src_gscale;
     int64_t R, C;
+    int span;                  // consecutive row tiles (of one column tile) per workgroup
     KArgs k;
     KArgs krow;                // DUAL: the row-wise operand produced from the same read
 };
@@ -279,6 +274,20 @@ __device__ __forceinline__ void decode_group_bf16(uint2 codes, uint32_t sc, uint
     }
 }
 
+// what one thread brings in for one tile
+template <bool PACKED>
+struct ColFetch {
+    uint4 v[4];                // bf16: 8 elements of rows (tid >> 3) + 32 * pass
+};
+template <>
+struct ColFetch<true> {
+    uint2 cw[2];               // packed: two groups of 16 codes of row tid >> 1 ...
+    uint32_t sc[2];            // ... and their scale bytes
+};
+
+// A workgroup takes `span` consecutive row tiles of one column tile (blockIdx.x = column tile, blockIdx.y = run of
+// row tiles): the scale set-up is paid once, the next tile's loads are in flight while the current one is quantized,
+// and the halves of an output line (128 source rows give 64 bytes of codes per column) are written close in time.
 // DUAL (bf16 source only): the tile's rows are also quantized row-wise (groups along C) while they pass through
 // registers on the way into LDS, so one read of the source yields both backward operands of dY (Q3 and Q5).
 template <int ROUND, bool SUP, bool PACKED, bool DUAL = false>
@@ -287,124 +296,171 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
     __shared__ __attribute__((aligned(16))) uint32_t tile[kTileR * 32];
     __shared__ float inv_tab[128];
     __shared__ float red[4];
+    __shared__ float os_sh[4];
     const int tid = threadIdx.x;
     const int64_t R = a.R, C = a.C;
-    // Workgroup ids are dealt round-robin over the 8 XCDs.  A packed source has only 32 bytes of codes per row and
-    // tile, so there each XCD gets a contiguous run of tiles (column tile fastest): neighbouring column tiles,
-    // which share the source's cache lines, then meet in one L2.
-    const int64_t tiles_c = (C + kTileC - 1) / kTileC, total = tiles_c * ((R + kTileR - 1) / kTileR);
-    int64_t tid_x = blockIdx.x;
-    {
-        const int64_t per_xcd = total / 8;
-        if (PACKED && tid_x < per_xcd * 8) tid_x = (tid_x & 7) * per_xcd + (tid_x >> 3);
+    const uint32_t tiles_r = (uint32_t)((R + kTileR - 1) / kTileR);
+    uint32_t bx = blockIdx.x, by = blockIdx.y;
+    if (PACKED) {
+        // Workgroup ids are dealt round-robin over the 8 XCDs.  A packed source has only 32 bytes of codes per row and
+        // tile, so there each XCD gets a contiguous run of workgroups (column tile fastest): neighbouring column
+        // tiles, which share the source's cache lines, then meet in one L2.
+        const uint32_t total = gridDim.x * gridDim.y, per_xcd = total / 8;
+        uint32_t lin = by * gridDim.x + bx;
+        if (lin < per_xcd * 8) lin = (lin & 7) * per_xcd + (lin >> 3);
+        by = lin / gridDim.x;
+        bx = lin - by * gridDim.x;
     }
-    const bool first_tile = tid_x == 0;
-    const int64_t R0 = (tid_x / tiles_c) * kTileR, C0 = (tid_x % tiles_c) * kTileC;
-    // the tile's data first: these loads do not depend on the scale set-up and overlap with it
-    uint4 vs[4];
-    if (!PACKED) {
-#pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-            const int64_t gr = R0 + pass * 32 + (tid >> 3), gc = C0 + (tid & 7) * 8;
-            vs[pass] = make_uint4(0, 0, 0, 0);
-            if (gr < R && gc < C) vs[pass] = ld_col(a.src + ((gr * C + gc) >> 3));
-        }
-    }
-    fill_inv_table(inv_tab);
-    const OuterScale os = outer_scale(block_tensor_amax(a.k, red));
-    if (first_tile && tid == 0) {
-        a.k.gscale[0] = os.S_g;
-        if (DUAL) a.krow.gscale[0] = os.S_g;
-    }
-    if (DUAL) __syncthreads();          // the reciprocal table is used in phase 1
+    const int64_t C0 = (int64_t)bx * kTileC;
+    const uint32_t rt0 = by * (uint32_t)a.span;
+    const int ntile = (int)min((uint32_t)a.span, tiles_r - rt0);
 
-    // phase 1: tile -> LDS as bf16 pairs, row-major with rotated columns
-    if (!PACKED) {
+    // ---- loads of one tile into registers (nothing here depends on the scale set-up)
+    const int64_t ld_row = PACKED ? (tid >> 1) : (tid >> 3);
+    const int64_t ld_col = C0 + (PACKED ? 32 * (tid & 1) : 8 * (tid & 7));
+    auto fetch = [&](int t, ColFetch<PACKED> &f) {
+        const int64_t R0 = (int64_t)(rt0 + t) * kTileR;
+        if constexpr (!PACKED) {
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-            const int row = pass * 32 + (tid >> 3), q = tid & 7;
-            const int64_t gr = R0 + row, gc = C0 + q * 8;
-            const bool valid = gr < R && gc < C;
-            const uint4 v = vs[pass];
-            *reinterpret_cast<uint4 *>(&tile[tile_pos(row, q * 4)]) = v;
-            if (DUAL) {
-                // row-wise: lanes q, q^1 hold one group of 16 along C
-                const uint32_t hm = absmax8_bits(v);
-                const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
-                const uint32_t bm = hm > o1 ? hm : o1;
-                const uint32_t sc = e4m3_round<SUP>(u2f(bm << 16) * os.inv_cg);
-                const float r = os.inv_sg * inv_tab[sc];
-                const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
-                                    bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-                const int64_t e0 = gr * C + gc;
-                const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 2), a.krow.k0, a.krow.k1);
-                if (valid) a.krow.codes[e0 >> 3] = qd;
-                const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
-                const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
-                if (valid && q == 0) {
-                    if ((C & 63) == 0) {
-                        *reinterpret_cast<uint32_t *>(a.krow.scales + (e0 >> 4)) = s4;
-                    } else {
-                        for (int b = 0; b < 4; ++b)
-                            if (gc + 16 * b < C) a.krow.scales[(e0 >> 4) + b] = (uint8_t)(s4 >> (8 * b));
-                    }
+            for (int pass = 0; pass < 4; ++pass) {
+                const int64_t gr = R0 + pass * 32 + ld_row;
+                f.v[pass] = make_uint4(0, 0, 0, 0);
+                if (gr < R && ld_col < C) f.v[pass] = ld_stream(a.src + ((gr * C + ld_col) >> 3));
+            }
+        } else {
+            const int64_t gr = R0 + ld_row;
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int64_t gc = ld_col + 16 * b;
+                f.cw[b] = make_uint2(0, 0);
+                f.sc[b] = 0;
+                if (gr < R && gc < C) {
+                    f.cw[b] = *reinterpret_cast<const uint2 *>(a.src_codes + ((gr * C + gc) >> 1));
+                    f.sc[b] = a.src_scales[(gr * C + gc) >> 4];
                 }
             }
         }
-    } else {
-        const int row = tid >> 1, half = tid & 1;
-        const int64_t gr = R0 + row;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int64_t gc = C0 + 32 * half + 16 * b;
-            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (gr < R && gc < C) {
-                const uint2 cw = *reinterpret_cast<const uint2 *>(a.src_codes + ((gr * C + gc) >> 1));
-                const uint32_t sc = a.src_scales[(gr * C + gc) >> 4];
-                decode_group_bf16(cw, sc, d);
+    };
+    ColFetch<PACKED> cur;
+    fetch(0, cur);
+
+    // ---- set-up, once per workgroup: reciprocal table (waves 0, 1), outer scale (wave 2)
+    fill_inv_table(inv_tab);
+    const float amax = block_tensor_amax(a.k, red);
+    if ((tid >> 6) == 2) {
+        const OuterScale o = outer_scale(amax);
+        if (tid == 128) {
+            os_sh[0] = o.S_g;
+            os_sh[1] = o.inv_sg;
+            os_sh[2] = o.inv_cg;
+            if (blockIdx.x == 0 && blockIdx.y == 0) {
+                a.k.gscale[0] = o.S_g;
+                if (DUAL) a.krow.gscale[0] = o.S_g;
             }
-            const int dw = 16 * half + 8 * b;
-            *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw)]) = make_uint4(d[0], d[1], d[2], d[3]);
-            *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw + 4)]) = make_uint4(d[4], d[5], d[6], d[7]);
         }
     }
     const float src_sg = PACKED ? a.src_gscale[0] : 1.0f;
     __syncthreads();
+    OuterScale os;
+    os.S_g = os_sh[0];
+    os.inv_sg = os_sh[1];
+    os.inv_cg = os_sh[2];
 
-    // phase 2: lane = (row group rb, column pair cp): 16 dwords down two columns
+    // phase-2 ownership: lane = (row group rb, column pair cp): 16 rows down two columns
     const int rb = tid & 7, cp = tid >> 3;
-    uint32_t w[16];
-    ushort2_t m2 = {0, 0};
+    const int64_t c_first = C0 + 2 * cp;
+    const int64_t out_lane = c_first * R + 16 * rb;        // + R0 (+ R for the second column): output element index
+
+    for (int t = 0; t < ntile; ++t) {
+        const int64_t R0 = (int64_t)(rt0 + t) * kTileR;
+        if (t > 0) __syncthreads();                         // everyone is done reading the previous tile
+        // phase 1: tile -> LDS as bf16 pairs, row-major with rotated columns
+        if constexpr (!PACKED) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        w[i] = tile[tile_pos(16 * rb + i, cp)];
-        m2 = __builtin_elementwise_max(m2, as_us2(w[i] & 0x7FFF7FFFu));
-    }
-    const int64_t k_first = R0 + 16 * rb;
-    if (k_first >= R) return;
+            for (int pass = 0; pass < 4; ++pass) {
+                const int row = pass * 32 + (tid >> 3), q = tid & 7;
+                const uint4 v = cur.v[pass];
+                *reinterpret_cast<uint4 *>(&tile[tile_pos(row, q * 4)]) = v;
+                if (DUAL) {
+                    // row-wise: lanes q, q^1 hold one group of 16 along C
+                    const int64_t gr = R0 + row;
+                    const bool valid = gr < R && ld_col < C;
+                    const uint32_t hm = absmax8_bits(v);
+                    const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
+                    const uint32_t bm = hm > o1 ? hm : o1;
+                    const uint32_t sc = e4m3_round<SUP>(u2f(bm << 16) * os.inv_cg);
+                    const float r = os.inv_sg * inv_tab[sc];
+                    const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                                        bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+                    const int64_t e0 = gr * C + ld_col;
+                    const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 2), a.krow.k0, a.krow.k1);
+                    if (valid) a.krow.codes[e0 >> 3] = qd;
+                    const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
+                    const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
+                    if (valid && q == 0) {
+                        if ((C & 63) == 0) {
+                            *reinterpret_cast<uint32_t *>(a.krow.scales + (e0 >> 4)) = s4;
+                        } else {
+                            for (int b = 0; b < 4; ++b)
+                                if (ld_col + 16 * b < C) a.krow.scales[(e0 >> 4) + b] = (uint8_t)(s4 >> (8 * b));
+                        }
+                    }
+                }
+            }
+        } else {
+            const int row = tid >> 1, half = tid & 1;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t c = C0 + 2 * cp + j;
-        if (c >= C) break;
-        float amax_b = u2f((uint32_t)(j == 0 ? m2.x : m2.y) << 16);
-        if (PACKED) amax_b = amax_b * src_sg;
-        const float s = amax_b * os.inv_cg;
-        const uint32_t sc = e4m3_round<SUP>(s);
-        const float r = os.inv_sg * inv_tab[sc];
-        float x0[8], x1[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            x0[i] = j == 0 ? bf16_lo(w[i]) : bf16_hi(w[i]);
-            x1[i] = j == 0 ? bf16_lo(w[8 + i]) : bf16_hi(w[8 + i]);
-            if (PACKED) { x0[i] = x0[i] * src_sg; x1[i] = x1[i] * src_sg; }
+            for (int b = 0; b < 2; ++b) {
+                uint32_t d[8];
+                decode_group_bf16(cur.cw[b], cur.sc[b], d);
+                const int dw = 16 * half + 8 * b;
+                *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw)]) = make_uint4(d[0], d[1], d[2], d[3]);
+                *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw + 4)]) = make_uint4(d[4], d[5], d[6], d[7]);
+            }
         }
-        const uint32_t quad0 = (uint32_t)((c * R + k_first) >> 2);
-        uint2 q;
-        q.x = quant8<ROUND, SUP>(x0, r, quad0, a.k.k0, a.k.k1);
-        q.y = quant8<ROUND, SUP>(x1, r, quad0 + 2, a.k.k0, a.k.k1);
-        *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(a.k.codes) + ((c * R + k_first) >> 1)) = q;
-        a.k.scales[(c * R + k_first) >> 4] = (uint8_t)sc;
+        __syncthreads();
+        if (t + 1 < ntile) fetch(t + 1, cur);               // in flight during phase 2
+
+        // phase 2
+        uint32_t w[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) w[i] = tile[tile_pos(16 * rb + i, cp)];
+        if (R0 + 16 * rb >= R) continue;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (c_first + j >= C) break;
+            float x0[8], x1[8];
+            float m = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                x0[i] = j == 0 ? bf16_lo(w[i]) : bf16_hi(w[i]);
+                x1[i] = j == 0 ? bf16_lo(w[8 + i]) : bf16_hi(w[8 + i]);
+                if (PACKED) { x0[i] = x0[i] * src_sg; x1[i] = x1[i] * src_sg; }
+                m = fmaxf(m, fmaxf(__builtin_fabsf(x0[i]), __builtin_fabsf(x1[i])));
+            }
+            const float s = m * os.inv_cg;
+            const uint32_t sc = e4m3_round<SUP>(s);
+            const float r = os.inv_sg * inv_tab[sc];
+            const int64_t e = out_lane + R0 + (j ? R : 0);
+            const uint32_t quad0 = (uint32_t)(e >> 2);
+            uint2 q;
+            q.x = quant8<ROUND, SUP>(x0, r, quad0, a.k.k0, a.k.k1);
+            q.y = quant8<ROUND, SUP>(x1, r, quad0 + 2, a.k.k0, a.k.k1);
+            *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(a.k.codes) + (e >> 1)) = q;
+            a.k.scales[e >> 4] = (uint8_t)sc;
+        }
     }
+}
+
+// grid of the column kernels: enough workgroups to fill the chip before a workgroup takes several tiles
+inline dim3 col_grid(ColArgs &a)
+{
+    const int64_t tiles_c = (a.C + kTileC - 1) / kTileC, tiles_r = (a.R + kTileR - 1) / kTileR;
+    int span = 4;
+    while (span > 1 && tiles_c * ((tiles_r + span - 1) / span) < 2048) span >>= 1;
+    while ((tiles_r + span - 1) / span > 65535) span <<= 1;      // grid.y limit
+    a.span = span;
+    return dim3((unsigned)tiles_c, (unsigned)((tiles_r + span - 1) / span));
 }
 
 KArgs make_kargs(const QuantParams &p, const QuantOut &o)
@@ -436,9 +492,9 @@ void launch_row_t(const void *src, int64_t nchunks, const KArgs &k, bool deq, hi
 }
 
 template <bool PACKED>
-void launch_col_t(const ColArgs &a, int rounding, int scale_up, hipStream_t st)
+void launch_col_t(ColArgs &a, int rounding, int scale_up, hipStream_t st)
 {
-    dim3 grid((unsigned)(((a.C + kTileC - 1) / kTileC) * ((a.R + kTileR - 1) / kTileR)));
+    const dim3 grid = col_grid(a);
     if (rounding == 0) {
         if (scale_up) hipLaunchKernelGGL((quant_col_kernel<0, true, PACKED>), grid, dim3(kThreads), 0, st, a);
         else          hipLaunchKernelGGL((quant_col_kernel<0, false, PACKED>), grid, dim3(kThreads), 0, st, a);
@@ -514,7 +570,7 @@ hipError_t launch_quant_dual_bf16(const void *src, int64_t R, int64_t C, const Q
     a.C = C;
     a.k = make_kargs(pcol, ocol);
     a.krow = make_kargs(prow, orow);
-    dim3 grid((unsigned)(((C + kTileC - 1) / kTileC) * ((R + kTileR - 1) / kTileR)));
+    const dim3 grid = col_grid(a);
     const int sel = (pcol.rounding << 1) | pcol.scale_up;
     switch (sel) {
         case 0: hipLaunchKernelGGL((quant_col_kernel<0, false, false, true>), grid, dim3(kThreads), 0, st, a); break;
