@@ -35,8 +35,9 @@
  *       "x + xi <= midpoint -> q1" is taken on a discrete uniform of 22 bits:
  *       with f = (a - q1)/D and L = floor(f * 2^22), a is rounded up iff
  *       u + L >= 2^22 for u uniform on {0..2^22-1}; so P(q2) = L / 2^22.  Below
- *       1 (the E2M1 subnormal range) a is first rounded to a multiple of 2^-23,
- *       which makes f * 2^22 an integer there; from 1 to 6 a binary32 value has
+ *       1 (the E2M1 subnormal range) a is first truncated to a multiple of 2^-23
+ *       (it loses less than 2^-23, 5e-7 of the grid step), which makes f * 2^22 an
+ *       integer there; from 1 to 6 a binary32 value has
  *       at most 22 bits below the E2M1 mantissa bit, so L = f * 2^22 exactly and
  *       the rounding is exactly unbiased on that image of a.
  *   R6  The 22 random bits of output element e (index in the quantized
@@ -156,7 +157,7 @@ int oracle_round_rtn(float a)
 /* Sec. 2.1 round_{FP4,S} with the discrete uniform of R5; u22 in [0, 2^22) */
 int oracle_round_sr(float a, uint32_t u22)
 {
-    if (a < 1.0f) a = rintf(a * 8388608.0f) * (1.0f / 8388608.0f);   /* R5: 2^-23 grid below 1 */
+    if (a < 1.0f) a = floorf(a * 8388608.0f) * (1.0f / 8388608.0f);  /* R5: 2^-23 grid below 1, toward zero */
     if (a >= 6.0f) return 7;
     int i1 = 0;
     for (int i = 0; i < 7; ++i)

@@ -96,8 +96,8 @@ __device__ __forceinline__ uint32_t e2m1_rtn_pair(uint32_t old, float y0, float 
 
 // Sec. 2.1 stochastic rounding of two values by the hardware's FP32 -> FP4 conversion with a random word.  Scaled
 // by 2^-126 a magnitude's binary32 pattern is its E2M1 pattern extended by 22 fraction bits (fixed point below 1,
-// where the denormalisation rounds to a multiple of 2^-23 of the value); the conversion adds 22 random bits to that
-// fraction, truncates and saturates at 6, so a value moves to its upper neighbour with probability frac exactly.
+// where bits of the value below 2^-23 are dropped); the conversion adds 22 random bits to that fraction, truncates
+// and saturates at 6, so a value moves to its upper neighbour with probability frac exactly.
 // The first value takes bits 31..10 of the random word, the second bits 30..9: the two draws of one conversion
 // share all but one bit, so a caller that wants independent draws converts twice and keeps one nibble of each.
 //

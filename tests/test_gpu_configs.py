@@ -1,0 +1,128 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+Every linear of a workload runs as nvfp4_linear_fwd + the fused nvfp4_linear_bwd with bf16 outputs and a
+caller-supplied workspace.  Checked against the CPU oracle:
+  * the forward operands Q1(X), Q2(W): every code, scale byte, outer scale and the dequantized maximum, bit for bit;
+  * the backward operands Q3..Q6 (nvfp4_quantize with the layer's stream ids): every byte;
+  * the fused backward's dX, dW are the bytes of the separate nvfp4_linear_bwd_dx / _dw calls;
+  * Y, dX, dW on sampled rows (all columns), within 2^-8 |ref| + 1e-6 sum_k |a||b| of the oracle's float64 product of
+    the same dequantized operands (bf16 output: its rounding alone is up to 2^-9 relative).
+The quantizer stress tensor is compared in full.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+tj = None
+SAMPLE_ROWS = 48
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _load():
+    global tj
+    import paper_2510_27527_amd as mod
+    tj = mod
+    mod.binding.lib()          # fails loudly if the HIP library is missing
+    yield
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def same_bytes(q_gpu, q_ref: oracle.NVFP4, what, check_amax=False):
+    torch.cuda.synchronize()
+    assert (q_gpu.rows, q_gpu.K) == (q_ref.rows, q_ref.K), what
+    assert np.array_equal(q_gpu.gscale.cpu().numpy().view(np.uint32).ravel(), q_ref.gscale.view(np.uint32).ravel()), what
+    sc = q_gpu.scales.cpu().numpy()
+    assert np.array_equal(sc, q_ref.scales), "%s: %d scale bytes differ" % (what, int((sc != q_ref.scales).sum()))
+    cd = q_gpu.codes.cpu().numpy()
+    assert np.array_equal(cd, q_ref.codes), "%s: %d code bytes differ" % (what, int((cd != q_ref.codes).sum()))
+    if check_amax:
+        assert np.float32(q_gpu.amax_deq.cpu().numpy()[0]) == np.float32(q_ref.amax_deq), what
+
+
+def product_ok(got_rows: torch.Tensor, ref, absref, what):
+    g = got_rows.double().cpu().numpy()
+    err = np.abs(g - ref)
+    tol = 2.0 ** -8 * np.abs(ref) + 1e-6 * absref + 1e-30
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), "%s: err %.3e tol %.3e at %s" % (what, err[worst], tol[worst], worst)
+
+
+def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed):
+    B = tj.binding
+    say("[%s %s] N=%d D=%d C=%d: inputs" % (cfg, name, N, D, C))
+    Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed, kind)
+    X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
+    ws = tj.alloc_workspace(max(tj.workspace_bytes(op, N, D, C) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD)))
+    Xq, Wq = tj.alloc_nvfp4(N, D), tj.alloc_nvfp4(C, D)
+    Y = torch.empty((N, C), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((C, D), dtype=torch.bfloat16, device="cuda")
+    tj.linear_fwd(X, W, B.OUT_BF16, Y=Y, Xq=Xq, Wq=Wq, ws=ws)
+    tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_BF16, dX=dX, dW=dW, ws=ws)
+    torch.cuda.synchronize()
+
+    say("[%s %s] oracle forward operands" % (cfg, name))
+    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    same_bytes(Xq, oXq, "Q1(X)", check_amax=True)
+    same_bytes(Wq, oWq, "Q2(W)", check_amax=True)
+    say("[%s %s] oracle backward operands" % (cfg, name))
+    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, sr_seed, li)
+    same_bytes(tj.quantize(dY, 0, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 3), o3, "Q3(dY)")
+    same_bytes(tj.quantize(Wq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 4), o4, "Q4(W_hat)")
+    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, sr_seed, li)
+    same_bytes(tj.quantize(dY, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 5), o5, "Q5(dY^T)")
+    same_bytes(tj.quantize(Xq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 6), o6, "Q6(X_hat)")
+    dX1 = tj.linear_bwd_dx(dY, Wq, sr_seed, li, B.OUT_BF16)
+    dW1 = tj.linear_bwd_dw(dY, Xq, sr_seed, li, B.OUT_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(dX, dX1) and torch.equal(dW, dW1), "fused backward differs from the separate calls"
+
+    rng = np.random.default_rng(seed)
+    for pname, got, qa, qb in (("Y", Y, oXq, oWq), ("dX", dX, o3, o4), ("dW", dW, o5, o6)):
+        say("[%s %s] oracle product %s on %d sampled rows" % (cfg, name, pname, min(SAMPLE_ROWS, qa.rows)))
+        rows = np.sort(rng.choice(qa.rows, min(SAMPLE_ROWS, qa.rows), replace=False))
+        rows[0], rows[-1] = 0, qa.rows - 1                        # the corners are always in
+        rows = np.unique(rows)
+        ref, absref = oracle.gemm_nt(qa, qb, rows_a=rows)
+        product_ok(got[torch.from_numpy(rows).cuda()], ref, absref, "%s %s %s" % (cfg, name, pname))
+
+
+def _cases(cfg):
+    return [pytest.param(cfg, li, id="%s-%s" % (cfg, lin[0])) for li, lin in enumerate(wl.config_linears(cfg))]
+
+
+@pytest.mark.parametrize("cfg,li", _cases("cfg2_block768") + _cases("cfg3_block1024") + _cases("cfg5_square8192"))
+def test_full_size_linear(cfg, li):
+    name, N, D, C, seed, kind = wl.config_linears(cfg)[li]
+    run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed=0)
+
+
+def test_quantizer_stress_full():
+    """8192 x 8192 Student-t(3) x 0.1: row-wise nearest and column-wise stochastic (seed 7), every byte."""
+    B = tj.binding
+    c = wl.CONFIGS["cfg4_quant_stress"]
+    bits = wl.student_t_bf16((c["rows"], c["cols"]), c["nu"], c["scale"], c["seed"])
+    x = dev_bf16(bits)
+    say("[cfg4] row-wise nearest")
+    same_bytes(tj.quantize(x, 0, B.ROUND_RTN), oracle.quantize_bf16(bits, 0, oracle.RTN), "row RTN", check_amax=True)
+    say("[cfg4] column-wise stochastic")
+    same_bytes(tj.quantize(x, 1, B.ROUND_SR, seed=7, tensor_id=5),
+               oracle.quantize_bf16(bits, 1, oracle.SR, seed=7, tensor_id=5), "col SR")
+    say("[cfg4] row-wise stochastic, 1 x 128 outer blocks")
+    same_bytes(tj.quantize(x, 0, B.ROUND_SR, seed=7, tensor_id=3, outer=B.OUTER_BLOCK128),
+               oracle.quantize_bf16(bits, 0, oracle.SR, seed=7, tensor_id=3, outer=oracle.OUTER_BLOCK128), "row SR block128")

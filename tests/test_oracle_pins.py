@@ -130,7 +130,7 @@ def test_sr_closed_form_probability(a):
     if a32 >= 6.0:
         assert lower.value == 7 and ups == 0
         return
-    a_img = float(np.rint(np.float64(a32) * 2.0 ** 23) / 2.0 ** 23) if a32 < 1.0 else a32   # R5: 2^-23 grid below 1
+    a_img = float(np.floor(np.float64(a32) * 2.0 ** 23) / 2.0 ** 23) if a32 < 1.0 else a32  # R5: 2^-23 grid below 1
     i1 = int(np.searchsorted(GRID, a_img, side="right") - 1)
     assert lower.value == i1
     q1, q2 = GRID[i1], GRID[i1 + 1]
