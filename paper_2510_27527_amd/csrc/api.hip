@@ -173,6 +173,72 @@ int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nv
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
+QuantParams params_of(const QuantPlan &pl, const nvfp4_qcfg *cfg)
+{
+    QuantParams p{};
+    p.rounding = pl.rounding;
+    p.scale_up = pl.scale_up ? 1 : 0;
+    p.outer = pl.outer;
+    const uint64_t key = stream_key(cfg->seed, cfg->tensor_id);
+    p.k0 = (uint32_t)key;
+    p.k1 = (uint32_t)(key >> 32);
+    return p;
+}
+
+void stamp(nvfp4_tensor *out, const QuantPlan &pl)
+{
+    out->rows = pl.out_rows;
+    out->K = pl.out_K;
+    out->outer_mode = pl.outer;
+}
+
+// Two row-wise tensor-mode quantizations of bf16 sources with the same settings (the two operands of a forward
+// call): one launch for both maxima, one for both quantizations.
+int run_quantize_row_pair(const void *src0, const QuantPlan &pl0, nvfp4_tensor *out0, float *partials0, const void *src1,
+                          const QuantPlan &pl1, nvfp4_tensor *out1, float *partials1, const nvfp4_qcfg *cfg,
+                          hipStream_t st)
+{
+    const bool pairable = pl0.src_kind == NVFP4_SRC_BF16 && pl1.src_kind == NVFP4_SRC_BF16 && pl0.axis == 0 &&
+                          pl1.axis == 0 && pl0.outer == NVFP4_OUTER_TENSOR && pl1.outer == NVFP4_OUTER_TENSOR &&
+                          cfg->amax_in == nullptr && pl0.R * pl0.C > 0 && pl1.R * pl1.C > 0;
+    if (!pairable) {
+        const int rc = run_quantize(src0, pl0, cfg, out0, partials0, st);
+        return rc ? rc : run_quantize(src1, pl1, cfg, out1, partials1, st);
+    }
+    QuantParams p0 = params_of(pl0, cfg), p1 = params_of(pl1, cfg);
+    QuantOut o0{out0->codes, out0->scales, out0->gscale, out0->amax_deq};
+    QuantOut o1{out1->codes, out1->scales, out1->gscale, out1->amax_deq};
+    if (pl0.rounding != NVFP4_ROUND_RTN) o0.amax_deq = o1.amax_deq = nullptr;
+    stamp(out0, pl0);
+    stamp(out1, pl1);
+    launch_amax_partials_pair(src0, pl0.R * pl0.C, partials0, o0.amax_deq, &p0.npart, src1, pl1.R * pl1.C, partials1,
+                              o1.amax_deq, &p1.npart, st);
+    p0.amax_partials = partials0;
+    p1.amax_partials = partials1;
+    const hipError_t e = launch_quant_row_bf16_pair(src0, pl0.R, pl0.C, p0, o0, src1, pl1.R, pl1.C, p1, o1, st);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+// Two column-wise re-quantizations of packed tensors (Q4 and Q6 of one backward call) in one launch.
+int run_requant_pair(const nvfp4_tensor *s0, const QuantPlan &pl0, const nvfp4_qcfg *c0, nvfp4_tensor *out0,
+                     const nvfp4_tensor *s1, const QuantPlan &pl1, const nvfp4_qcfg *c1, nvfp4_tensor *out1,
+                     hipStream_t st)
+{
+    QuantParams p0 = params_of(pl0, c0), p1 = params_of(pl1, c1);
+    p0.amax_scalar = c0->amax_in ? c0->amax_in : s0->amax_deq;
+    p1.amax_scalar = c1->amax_in ? c1->amax_in : s1->amax_deq;
+    if (p0.rounding != p1.rounding || p0.scale_up != p1.scale_up) {
+        const int rc = run_quantize(s0, pl0, c0, out0, nullptr, st);
+        return rc ? rc : run_quantize(s1, pl1, c1, out1, nullptr, st);
+    }
+    stamp(out0, pl0);
+    stamp(out1, pl1);
+    QuantOut o0{out0->codes, out0->scales, out0->gscale, nullptr}, o1{out1->codes, out1->scales, out1->gscale, nullptr};
+    PackedSrc ps0{s0->codes, s0->scales, s0->gscale, s0->outer_mode}, ps1{s1->codes, s1->scales, s1->gscale, s1->outer_mode};
+    const hipError_t e = launch_requant_col_pair(ps0, pl0.R, pl0.C, p0, o0, ps1, pl1.R, pl1.C, p1, o1, st);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
 int run_gemm(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *ws, size_t ws_bytes,
              hipStream_t st)
 {
@@ -325,9 +391,7 @@ int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t
     float *part_w = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
     const size_t gbytes = gemm_workspace_bytes(N, C, D);
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
-    rc = run_quantize(X, px, &cfg, Xq_ctx, part_x, st);
-    if (rc) return rc;
-    rc = run_quantize(W, pw, &cfg, Wq_ctx, part_w, st);
+    rc = run_quantize_row_pair(X, px, Xq_ctx, part_x, W, pw, Wq_ctx, part_w, &cfg, st);
     if (rc) return rc;
     return run_gemm(Xq_ctx, Wq_ctx, Y, out_dtype, gws, gbytes, st);
 }
@@ -459,12 +523,13 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (N > 0 && C > 0) {
+        // every workgroup of the quantizer reduces the partial maxima itself: no launch in between
         const int npart = launch_amax_partials(dY, N * C, part, nullptr, st);
-        launch_amax_final(part, npart, amax, st);
         QuantParams pr{}, pc{};
         pr.rounding = pc.rounding = 1;
         pr.scale_up = pc.scale_up = 1;
-        pr.amax_scalar = pc.amax_scalar = amax;
+        pr.amax_partials = pc.amax_partials = part;
+        pr.npart = pc.npart = npart;
         const uint64_t k3 = stream_key(seed, c[0].tensor_id), k5 = stream_key(seed, c[2].tensor_id);
         pr.k0 = (uint32_t)k3; pr.k1 = (uint32_t)(k3 >> 32);
         pc.k0 = (uint32_t)k5; pc.k1 = (uint32_t)(k5 >> 32);
@@ -472,11 +537,9 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
         if (launch_quant_dual_bf16(dY, N, C, pr, orow, pc, ocol, st) != hipSuccess) return NVFP4_ERR_HIP;
     }
     q3.rows = N; q3.K = C; q5.rows = C; q5.K = N;
-    rc = run_quantize(Wq_ctx, p4, &c[1], &q4, nullptr, st);
+    rc = run_requant_pair(Wq_ctx, p4, &c[1], &q4, Xq_ctx, p6, &c[3], &q6, st);
     if (rc) return rc;
     rc = run_gemm(&q3, &q4, dX, out_dtype, gws, gbytes, st);
-    if (rc) return rc;
-    rc = run_quantize(Xq_ctx, p6, &c[3], &q6, nullptr, st);
     if (rc) return rc;
     return run_gemm(&q5, &q6, dW, out_dtype, gws, gbytes, st);
 }

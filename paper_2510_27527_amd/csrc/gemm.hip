@@ -20,6 +20,7 @@ namespace tj {
 namespace {
 
 constexpr int kThreads = 256;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 struct GemmArgs {
     const uint8_t *a_codes, *a_scales;
@@ -112,6 +113,10 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
     constexpr int SC_BYTES = PS ? ROWS * 16 : ROWS * NC * 4;   // one scale buffer (a pair of stages / one stage)
     constexpr int SC_BASE = 3 * CODE_BYTES;
     constexpr int STEPS = NC * 4;
+    // bf16 output: the MFMA takes the B fragment as its row operand, so that a lane ends up with runs of four
+    // consecutive output columns (8-byte stores); FP32 output keeps lanes along the columns (128 contiguous bytes
+    // per row and store instruction)
+    constexpr bool SWAP = OUT == 0;
     static_assert(!PS || NC == 2, "paired scale fetch assumes two chunks per stage");
     static_assert(NC % 2 == 0, "chunk parity must repeat per stage");
     static_assert(LA >= 1 && LB >= 1 && (PS || LS >= 1) && (ROWS * NC) % kThreads == 0, "tile too small");
@@ -336,7 +341,8 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].a[i], op[gs & 1].b[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].b[j], op[gs & 1].a[i], acc[i][j], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].a[i], op[gs & 1].b[j], acc[i][j], 0, 0, 0);
                 // issue order: one MFMA, then (in the steps that fetch raw fragments) two LDS reads, then its
                 // share of the expansion's VALU instructions
                 const bool fetch = (ks == 1 && c + 1 < NC) || gs == STEPS - 2;
@@ -355,28 +361,56 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
         __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the look-ahead loads before the LDS is released
     }
 
-    // epilogue: acc element e of lane: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
     constexpr bool SPLIT = OUT == 2;
     float alpha = 1.0f;
     if (!SPLIT) alpha = g.a_gscale[0] * g.b_gscale[0] * 256.0f;
-    float *outf = reinterpret_cast<float *>(g.out);
-    if (SPLIT) outf += (int64_t)blockIdx.z * g.M * g.N;
-    uint16_t *outh = reinterpret_cast<uint16_t *>(g.out);
+    if (SWAP) {
+        // a lane holds one output row (m = lane % 32) and, per 32 x 32 block, four runs of four consecutive columns
+        // (n = 8 * (e / 4) + 4 * (lane / 32) + e % 4): each run leaves as one 8-byte store
+        uint16_t *outh = reinterpret_cast<uint16_t *>(g.out);
+        const bool vec = (g.N & 3) == 0;             // then every run is aligned and entirely inside or outside
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = m0 + (wm * TM + i) * 32 + lr;
+            if (m >= g.M) continue;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t n = n0 + (wn * TN + j) * 32 + lr;
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * kg + (e & 3);
-                if (m < g.M && n < g.N) {
-                    const float v = acc[i][j][e] * alpha;
-                    if (OUT != 0) outf[m * g.N + n] = v;
-                    else outh[m * g.N + n] = (uint16_t)f32_to_bf16_bits(v);
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t n = n0 + (wn * TN + j) * 32 + 8 * q + 4 * kg;
+                    const float v0 = acc[i][j][4 * q] * alpha, v1 = acc[i][j][4 * q + 1] * alpha;
+                    const float v2 = acc[i][j][4 * q + 2] * alpha, v3 = acc[i][j][4 * q + 3] * alpha;
+                    if (vec) {
+                        if (n < g.N) {
+                            const bf16x2_t lo = __builtin_convertvector((float2_t){v0, v1}, bf16x2_t);
+                            const bf16x2_t hi = __builtin_convertvector((float2_t){v2, v3}, bf16x2_t);
+                            *reinterpret_cast<uint2 *>(outh + m * g.N + n) =
+                                make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+                        }
+                    } else {
+                        const float v[4] = {v0, v1, v2, v3};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (n + t < g.N) outh[m * g.N + n + t] = (uint16_t)f32_to_bf16_bits(v[t]);
+                    }
+                }
+        }
+    } else {
+        // acc element e of a lane: row 8 * (e / 4) + 4 * (lane / 32) + e % 4, column lane % 32
+        float *outf = reinterpret_cast<float *>(g.out);
+        if (SPLIT) outf += (int64_t)blockIdx.z * g.M * g.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t n = n0 + (wn * TN + j) * 32 + lr;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * kg + (e & 3);
+                    if (m < g.M && n < g.N) outf[m * g.N + n] = acc[i][j][e] * alpha;
                 }
             }
-        }
+    }
 }
 
 // sum the split-K partials in split order, scale, convert

@@ -37,6 +37,10 @@ struct PackedSrc {
 // partial maxima of |x| over a bf16 array of n elements (n % 8 == 0); returns the number of partials written;
 // zero_me (optional) is a device float the kernel also clears
 int launch_amax_partials(const void *src, int64_t n, float *partials, float *zero_me, hipStream_t st);
+// the same for two arrays in one launch
+void launch_amax_partials_pair(const void *src0, int64_t n0, float *partials0, float *zero0, int *npart0,
+                               const void *src1, int64_t n1, float *partials1, float *zero1, int *npart1,
+                               hipStream_t st);
 // reduce partials to one scalar
 void launch_amax_final(const float *partials, int npart, float *out, hipStream_t st);
 // zero one float
@@ -45,6 +49,10 @@ void launch_zero_scalar(float *p, hipStream_t st);
 // row-wise quantization of a bf16 [rows x K] array (groups along K)
 hipError_t launch_quant_row_bf16(const void *src, int64_t rows, int64_t K, const QuantParams &p, const QuantOut &o,
                                  hipStream_t st);
+// two such quantizations (same rounding mode, scale rounding and outer mode) in one launch
+hipError_t launch_quant_row_bf16_pair(const void *src0, int64_t rows0, int64_t K0, const QuantParams &p0,
+                                      const QuantOut &o0, const void *src1, int64_t rows1, int64_t K1,
+                                      const QuantParams &p1, const QuantOut &o1, hipStream_t st);
 // column-wise quantization of a bf16 [R x C] array: output [C x R] grouped along R
 hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
                                  hipStream_t st);
@@ -55,6 +63,11 @@ hipError_t launch_quant_dual_bf16(const void *src, int64_t R, int64_t C, const Q
 // column-wise re-quantization of an NVFP4 [R x C] tensor: output [C x R] grouped along R
 hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
                               hipStream_t st);
+
+// two such re-quantizations (same rounding mode and scale rounding) in one launch
+hipError_t launch_requant_col_pair(const PackedSrc &src0, int64_t R0, int64_t C0, const QuantParams &p0,
+                                   const QuantOut &o0, const PackedSrc &src1, int64_t R1, int64_t C1,
+                                   const QuantParams &p1, const QuantOut &o1, hipStream_t st);
 
 struct GemmOperand {
     const uint8_t *codes;

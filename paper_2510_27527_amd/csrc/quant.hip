@@ -111,14 +111,29 @@ __device__ __forceinline__ void publish_deq_max(float v, float *dst, float *red)
 
 // ------------------------------------------------------------------------------- amax ----
 
-__global__ __launch_bounds__(kThreads) void amax_partials_kernel(const uint4 *__restrict__ src, int64_t nchunks,
-                                                                 float *__restrict__ partials, float *zero_me)
+// One launch can serve two tensors (the two operands of a forward call): workgroups [0, j0.nblocks) take the first
+// job, the rest the second.
+struct AmaxJob {
+    const uint4 *src;
+    int64_t nchunks;
+    float *partials;
+    float *zero_me;       // optional: a float this launch also clears
+    unsigned nblocks;
+};
+
+__global__ __launch_bounds__(kThreads) void amax_partials_kernel(AmaxJob j0, AmaxJob j1)
 {
     __shared__ float red[4];
-    if (zero_me && blockIdx.x == 0 && threadIdx.x == 0) zero_me[0] = 0.0f;
+    const bool second = blockIdx.x >= j0.nblocks;
+    const uint4 *__restrict__ src = second ? j1.src : j0.src;
+    const int64_t nchunks = second ? j1.nchunks : j0.nchunks;
+    float *partials = second ? j1.partials : j0.partials;
+    float *zero_me = second ? j1.zero_me : j0.zero_me;
+    const unsigned bid = second ? blockIdx.x - j0.nblocks : blockIdx.x, nb = second ? j1.nblocks : j0.nblocks;
+    if (zero_me && bid == 0 && threadIdx.x == 0) zero_me[0] = 0.0f;
     uint32_t m = 0;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t stride = (int64_t)nb * kThreads;
+    int64_t c = (int64_t)bid * kThreads + threadIdx.x;
     for (; c + 3 * stride < nchunks; c += 4 * stride) {
         uint4 v0 = src[c], v1 = src[c + stride], v2 = src[c + 2 * stride], v3 = src[c + 3 * stride];
         uint32_t a = absmax8_bits(v0), b = absmax8_bits(v1), d = absmax8_bits(v2), e = absmax8_bits(v3);
@@ -133,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void amax_partials_kernel(const uint4 *__
     float f = wave_max(u2f(m << 16));
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = f;
     __syncthreads();
-    if (threadIdx.x == 0) partials[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    if (threadIdx.x == 0) partials[bid] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
 __global__ __launch_bounds__(kThreads) void amax_final_kernel(const float *__restrict__ partials, int npart,
@@ -152,15 +167,27 @@ __global__ void zero_scalar_kernel(float *p) { p[0] = 0.0f; }
 
 // ---------------------------------------------------------------------------- row-wise ----
 
+struct RowJob {
+    const uint4 *src;
+    int64_t nchunks;
+    KArgs a;
+};
+
+// first_second: first workgroup of the second job (0xFFFFFFFF when the launch has one job)
 template <int ROUND, bool SUP, int OUTER, bool DEQ>
-__global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__restrict__ src, int64_t nchunks, KArgs a)
+__global__ __launch_bounds__(kThreads) void quant_row_kernel(RowJob j0, RowJob j1, unsigned first_second)
 {
     __shared__ float inv_tab[128];
     __shared__ float red[4];
     const int tid = threadIdx.x;
+    const bool second = blockIdx.x >= first_second;
+    const uint4 *__restrict__ src = second ? j1.src : j0.src;
+    const int64_t nchunks = second ? j1.nchunks : j0.nchunks;
+    const KArgs a = second ? j1.a : j0.a;
+    const unsigned bid = second ? blockIdx.x - first_second : blockIdx.x;
     // the workgroup's data first: these loads do not depend on the scale set-up below and overlap with it
-    const int64_t c0 = (int64_t)blockIdx.x * kRowIter * kThreads + tid;
-    const bool full = ((int64_t)blockIdx.x + 1) * kRowIter * kThreads <= nchunks;
+    const int64_t c0 = (int64_t)bid * kRowIter * kThreads + tid;
+    const bool full = ((int64_t)bid + 1) * kRowIter * kThreads <= nchunks;
     uint4 vs[kRowIter];
 #pragma unroll
     for (int it = 0; it < kRowIter; ++it) {
@@ -172,14 +199,14 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(const uint4 *__rest
     // Largest dequantized magnitude.  In tensor mode the group holding the tensor maximum always gets
     // the scale 448 and its largest element the code 6, so the maximum is 6 * 448 * S_g in closed form;
     // only a floored S_g (maximum below 2688 * 2^-100) needs the reduction over all groups.
-    bool reduce_deq = DEQ && OUTER == 1;
+    bool reduce_deq = DEQ && OUTER == 1 && a.amax_deq != nullptr;
     if (OUTER == 0) {
         const float amax = block_tensor_amax(a, red);
         os = outer_scale(amax);
-        if (blockIdx.x == 0 && tid == 0) a.gscale[0] = os.S_g;
+        if (bid == 0 && tid == 0) a.gscale[0] = os.S_g;
         if (DEQ) {
-            reduce_deq = os.S_g == 0x1p-100f;
-            if (!reduce_deq && blockIdx.x == 0 && tid == 0) a.amax_deq[0] = amax == 0.0f ? 0.0f : 2688.0f * os.S_g;
+            reduce_deq = a.amax_deq != nullptr && os.S_g == 0x1p-100f;
+            if (!reduce_deq && a.amax_deq && bid == 0 && tid == 0) a.amax_deq[0] = amax == 0.0f ? 0.0f : 2688.0f * os.S_g;
         }
     }
     __syncthreads();
@@ -291,26 +318,30 @@ struct ColFetch<true> {
 // DUAL (bf16 source only): the tile's rows are also quantized row-wise (groups along C) while they pass through
 // registers on the way into LDS, so one read of the source yields both backward operands of dY (Q3 and Q5).
 template <int ROUND, bool SUP, bool PACKED, bool DUAL = false>
-__global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
+__global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs a1, unsigned first_second)
 {
     __shared__ __attribute__((aligned(16))) uint32_t tile[kTileR * 32];
     __shared__ float inv_tab[128];
     __shared__ float red[4];
     __shared__ float os_sh[4];
     const int tid = threadIdx.x;
+    // one launch can serve two tensors: workgroups from first_second on take the second job
+    const bool second = blockIdx.x >= first_second;
+    const ColArgs a = second ? a1 : a0;
+    const uint32_t lin0 = second ? blockIdx.x - first_second : blockIdx.x;
     const int64_t R = a.R, C = a.C;
     const uint32_t tiles_r = (uint32_t)((R + kTileR - 1) / kTileR);
-    uint32_t bx = blockIdx.x, by = blockIdx.y;
+    const uint32_t gx = (uint32_t)((C + kTileC - 1) / kTileC);              // column tiles
+    const uint32_t gy = (tiles_r + (uint32_t)a.span - 1) / (uint32_t)a.span; // runs of row tiles
+    uint32_t lin = lin0;
     if (PACKED) {
         // Workgroup ids are dealt round-robin over the 8 XCDs.  A packed source has only 32 bytes of codes per row and
         // tile, so there each XCD gets a contiguous run of workgroups (column tile fastest): neighbouring column
         // tiles, which share the source's cache lines, then meet in one L2.
-        const uint32_t total = gridDim.x * gridDim.y, per_xcd = total / 8;
-        uint32_t lin = by * gridDim.x + bx;
+        const uint32_t per_xcd = gx * gy / 8;
         if (lin < per_xcd * 8) lin = (lin & 7) * per_xcd + (lin >> 3);
-        by = lin / gridDim.x;
-        bx = lin - by * gridDim.x;
     }
+    const uint32_t by = lin / gx, bx = lin - by * gx;
     const int64_t C0 = (int64_t)bx * kTileC;
     const uint32_t rt0 = by * (uint32_t)a.span;
     const int ntile = (int)min((uint32_t)a.span, tiles_r - rt0);
@@ -353,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
             os_sh[0] = o.S_g;
             os_sh[1] = o.inv_sg;
             os_sh[2] = o.inv_cg;
-            if (blockIdx.x == 0 && blockIdx.y == 0) {
+            if (lin0 == 0) {
                 a.k.gscale[0] = o.S_g;
                 if (DUAL) a.krow.gscale[0] = o.S_g;
             }
@@ -452,15 +483,15 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a)
     }
 }
 
-// grid of the column kernels: enough workgroups to fill the chip before a workgroup takes several tiles
-inline dim3 col_grid(ColArgs &a)
+// number of workgroups of a column job (and its span): enough workgroups to fill the chip before a workgroup takes
+// several tiles
+inline unsigned col_grid(ColArgs &a)
 {
     const int64_t tiles_c = (a.C + kTileC - 1) / kTileC, tiles_r = (a.R + kTileR - 1) / kTileR;
     int span = 4;
     while (span > 1 && tiles_c * ((tiles_r + span - 1) / span) < 2048) span >>= 1;
-    while ((tiles_r + span - 1) / span > 65535) span <<= 1;      // grid.y limit
     a.span = span;
-    return dim3((unsigned)tiles_c, (unsigned)((tiles_r + span - 1) / span));
+    return (unsigned)(tiles_c * ((tiles_r + span - 1) / span));
 }
 
 KArgs make_kargs(const QuantParams &p, const QuantOut &o)
@@ -479,41 +510,59 @@ KArgs make_kargs(const QuantParams &p, const QuantOut &o)
 }
 
 template <int ROUND, bool SUP, int OUTER>
-void launch_row_t(const void *src, int64_t nchunks, const KArgs &k, bool deq, hipStream_t st)
+void launch_row_t(const RowJob &j0, const RowJob &j1, bool deq, hipStream_t st)
 {
     const int64_t per_wg = (int64_t)kThreads * kRowIter;
-    const unsigned grid = (unsigned)((nchunks + per_wg - 1) / per_wg);
+    const unsigned g0 = (unsigned)((j0.nchunks + per_wg - 1) / per_wg), g1 = (unsigned)((j1.nchunks + per_wg - 1) / per_wg);
+    const unsigned first_second = g1 ? g0 : 0xFFFFFFFFu;
     if (deq)
-        hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, OUTER, true>), dim3(grid), dim3(kThreads), 0, st,
-                           reinterpret_cast<const uint4 *>(src), nchunks, k);
+        hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, OUTER, true>), dim3(g0 + g1), dim3(kThreads), 0, st, j0, j1,
+                           first_second);
     else
-        hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, OUTER, false>), dim3(grid), dim3(kThreads), 0, st,
-                           reinterpret_cast<const uint4 *>(src), nchunks, k);
+        hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, OUTER, false>), dim3(g0 + g1), dim3(kThreads), 0, st, j0, j1,
+                           first_second);
 }
 
 template <bool PACKED>
-void launch_col_t(ColArgs &a, int rounding, int scale_up, hipStream_t st)
+void launch_col_t(ColArgs &a0, ColArgs &a1, bool pair, int rounding, int scale_up, hipStream_t st)
 {
-    const dim3 grid = col_grid(a);
+    const unsigned g0 = col_grid(a0), g1 = pair ? col_grid(a1) : 0;
+    const unsigned first_second = pair ? g0 : 0xFFFFFFFFu;
+    const dim3 grid(g0 + g1);
     if (rounding == 0) {
-        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<0, true, PACKED>), grid, dim3(kThreads), 0, st, a);
-        else          hipLaunchKernelGGL((quant_col_kernel<0, false, PACKED>), grid, dim3(kThreads), 0, st, a);
+        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<0, true, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        else          hipLaunchKernelGGL((quant_col_kernel<0, false, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
     } else {
-        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<1, true, PACKED>), grid, dim3(kThreads), 0, st, a);
-        else          hipLaunchKernelGGL((quant_col_kernel<1, false, PACKED>), grid, dim3(kThreads), 0, st, a);
+        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<1, true, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        else          hipLaunchKernelGGL((quant_col_kernel<1, false, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
     }
 }
 
 }  // namespace
 
+static int amax_grid(int64_t nchunks)
+{
+    const int64_t want = (nchunks + (int64_t)kThreads * 8 - 1) / ((int64_t)kThreads * 8);
+    return (int)(want < 1 ? 1 : (want > kMaxAmaxPartials ? kMaxAmaxPartials : want));
+}
+
 int launch_amax_partials(const void *src, int64_t n, float *partials, float *zero_me, hipStream_t st)
 {
-    const int64_t nchunks = n / 8;
-    int64_t want = (nchunks + (int64_t)kThreads * 8 - 1) / ((int64_t)kThreads * 8);
-    int grid = (int)(want < 1 ? 1 : (want > kMaxAmaxPartials ? kMaxAmaxPartials : want));
-    hipLaunchKernelGGL(amax_partials_kernel, dim3(grid), dim3(kThreads), 0, st,
-                       reinterpret_cast<const uint4 *>(src), nchunks, partials, zero_me);
-    return grid;
+    AmaxJob j0{reinterpret_cast<const uint4 *>(src), n / 8, partials, zero_me, (unsigned)amax_grid(n / 8)};
+    AmaxJob j1{};
+    hipLaunchKernelGGL(amax_partials_kernel, dim3(j0.nblocks), dim3(kThreads), 0, st, j0, j1);
+    return (int)j0.nblocks;
+}
+
+void launch_amax_partials_pair(const void *src0, int64_t n0, float *partials0, float *zero0, int *npart0,
+                               const void *src1, int64_t n1, float *partials1, float *zero1, int *npart1,
+                               hipStream_t st)
+{
+    AmaxJob j0{reinterpret_cast<const uint4 *>(src0), n0 / 8, partials0, zero0, (unsigned)amax_grid(n0 / 8)};
+    AmaxJob j1{reinterpret_cast<const uint4 *>(src1), n1 / 8, partials1, zero1, (unsigned)amax_grid(n1 / 8)};
+    hipLaunchKernelGGL(amax_partials_kernel, dim3(j0.nblocks + j1.nblocks), dim3(kThreads), 0, st, j0, j1);
+    *npart0 = (int)j0.nblocks;
+    *npart1 = (int)j1.nblocks;
 }
 
 void launch_amax_final(const float *partials, int npart, float *out, hipStream_t st)
@@ -526,24 +575,40 @@ void launch_zero_scalar(float *p, hipStream_t st)
     hipLaunchKernelGGL(zero_scalar_kernel, dim3(1), dim3(1), 0, st, p);
 }
 
+static void launch_row_sel(const RowJob &j0, const RowJob &j1, const QuantParams &p, bool deq, hipStream_t st)
+{
+    const int sel = (p.rounding << 2) | (p.scale_up << 1) | p.outer;
+    switch (sel) {
+        case 0: launch_row_t<0, false, 0>(j0, j1, deq, st); break;
+        case 1: launch_row_t<0, false, 1>(j0, j1, deq, st); break;
+        case 2: launch_row_t<0, true, 0>(j0, j1, deq, st); break;
+        case 3: launch_row_t<0, true, 1>(j0, j1, deq, st); break;
+        case 4: launch_row_t<1, false, 0>(j0, j1, false, st); break;
+        case 5: launch_row_t<1, false, 1>(j0, j1, false, st); break;
+        case 6: launch_row_t<1, true, 0>(j0, j1, false, st); break;
+        default: launch_row_t<1, true, 1>(j0, j1, false, st); break;
+    }
+}
+
 hipError_t launch_quant_row_bf16(const void *src, int64_t rows, int64_t K, const QuantParams &p, const QuantOut &o,
                                  hipStream_t st)
 {
     const int64_t nchunks = rows * K / 8;
     if (nchunks == 0) return hipSuccess;
-    const KArgs k = make_kargs(p, o);
-    const bool deq = o.amax_deq != nullptr && p.rounding == 0;
-    const int sel = (p.rounding << 2) | (p.scale_up << 1) | p.outer;
-    switch (sel) {
-        case 0: launch_row_t<0, false, 0>(src, nchunks, k, deq, st); break;
-        case 1: launch_row_t<0, false, 1>(src, nchunks, k, deq, st); break;
-        case 2: launch_row_t<0, true, 0>(src, nchunks, k, deq, st); break;
-        case 3: launch_row_t<0, true, 1>(src, nchunks, k, deq, st); break;
-        case 4: launch_row_t<1, false, 0>(src, nchunks, k, false, st); break;
-        case 5: launch_row_t<1, false, 1>(src, nchunks, k, false, st); break;
-        case 6: launch_row_t<1, true, 0>(src, nchunks, k, false, st); break;
-        default: launch_row_t<1, true, 1>(src, nchunks, k, false, st); break;
-    }
+    RowJob j0{reinterpret_cast<const uint4 *>(src), nchunks, make_kargs(p, o)}, j1{};
+    launch_row_sel(j0, j1, p, o.amax_deq != nullptr && p.rounding == 0, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_quant_row_bf16_pair(const void *src0, int64_t rows0, int64_t K0, const QuantParams &p0,
+                                      const QuantOut &o0, const void *src1, int64_t rows1, int64_t K1,
+                                      const QuantParams &p1, const QuantOut &o1, hipStream_t st)
+{
+    if (rows0 * K0 == 0) return launch_quant_row_bf16(src1, rows1, K1, p1, o1, st);
+    if (rows1 * K1 == 0) return launch_quant_row_bf16(src0, rows0, K0, p0, o0, st);
+    RowJob j0{reinterpret_cast<const uint4 *>(src0), rows0 * K0 / 8, make_kargs(p0, o0)};
+    RowJob j1{reinterpret_cast<const uint4 *>(src1), rows1 * K1 / 8, make_kargs(p1, o1)};
+    launch_row_sel(j0, j1, p0, (o0.amax_deq != nullptr || o1.amax_deq != nullptr) && p0.rounding == 0, st);
     return hipGetLastError();
 }
 
@@ -556,7 +621,8 @@ hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const Qu
     a.R = R;
     a.C = C;
     a.k = make_kargs(p, o);
-    launch_col_t<false>(a, p.rounding, p.scale_up, st);
+    ColArgs none{};
+    launch_col_t<false>(a, none, false, p.rounding, p.scale_up, st);
     return hipGetLastError();
 }
 
@@ -570,21 +636,21 @@ hipError_t launch_quant_dual_bf16(const void *src, int64_t R, int64_t C, const Q
     a.C = C;
     a.k = make_kargs(pcol, ocol);
     a.krow = make_kargs(prow, orow);
-    const dim3 grid = col_grid(a);
+    const dim3 grid(col_grid(a));
+    const ColArgs none{};
+    const unsigned fs = 0xFFFFFFFFu;
     const int sel = (pcol.rounding << 1) | pcol.scale_up;
     switch (sel) {
-        case 0: hipLaunchKernelGGL((quant_col_kernel<0, false, false, true>), grid, dim3(kThreads), 0, st, a); break;
-        case 1: hipLaunchKernelGGL((quant_col_kernel<0, true, false, true>), grid, dim3(kThreads), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((quant_col_kernel<1, false, false, true>), grid, dim3(kThreads), 0, st, a); break;
-        default: hipLaunchKernelGGL((quant_col_kernel<1, true, false, true>), grid, dim3(kThreads), 0, st, a); break;
+        case 0: hipLaunchKernelGGL((quant_col_kernel<0, false, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
+        case 1: hipLaunchKernelGGL((quant_col_kernel<0, true, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
+        case 2: hipLaunchKernelGGL((quant_col_kernel<1, false, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
+        default: hipLaunchKernelGGL((quant_col_kernel<1, true, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
-                              hipStream_t st)
+static ColArgs packed_args(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o)
 {
-    if (R == 0 || C == 0) return hipSuccess;
     ColArgs a{};
     a.src_codes = src.codes;
     a.src_scales = src.scales;
@@ -592,7 +658,26 @@ hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const 
     a.R = R;
     a.C = C;
     a.k = make_kargs(p, o);
-    launch_col_t<true>(a, p.rounding, p.scale_up, st);
+    return a;
+}
+
+hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const QuantParams &p, const QuantOut &o,
+                              hipStream_t st)
+{
+    if (R == 0 || C == 0) return hipSuccess;
+    ColArgs a = packed_args(src, R, C, p, o), none{};
+    launch_col_t<true>(a, none, false, p.rounding, p.scale_up, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_requant_col_pair(const PackedSrc &src0, int64_t R0, int64_t C0, const QuantParams &p0,
+                                   const QuantOut &o0, const PackedSrc &src1, int64_t R1, int64_t C1,
+                                   const QuantParams &p1, const QuantOut &o1, hipStream_t st)
+{
+    if (R0 == 0 || C0 == 0) return launch_requant_col(src1, R1, C1, p1, o1, st);
+    if (R1 == 0 || C1 == 0) return launch_requant_col(src0, R0, C0, p0, o0, st);
+    ColArgs a0 = packed_args(src0, R0, C0, p0, o0), a1 = packed_args(src1, R1, C1, p1, o1);
+    launch_col_t<true>(a0, a1, true, p0.rounding, p0.scale_up, st);
     return hipGetLastError();
 }
 
