@@ -35,20 +35,20 @@ struct GemmArgs {
 
 __device__ __forceinline__ half2_t scale_pair(uint32_t sc)
 {
-    // E4M3 byte << 7 is the FP16 pattern of S_block * 2^-8 (same field layout, bias 15 vs 7);
-    // times 16 gives S_block * 2^-4, normal in FP16 for every code
-    const uint32_t bits = sc * 0x00800080u;
-    const half2_t sixteen = {(_Float16)16.0f, (_Float16)16.0f};
-    return __builtin_bit_cast(half2_t, bits) * sixteen;
+    // E4M3 byte << 7 is the FP16 pattern of S_block * 2^-8 (same field layout, bias 15 vs 7; E4M3 subnormals become
+    // FP16 subnormals of the same value)
+    return __builtin_bit_cast(half2_t, sc * 0x00800080u);
 }
 
-// eight codes (one dword) times the block scale -> eight FP16
+// eight codes (one dword) times the block scale -> eight FP16 holding P * S_block * 2^-4.  The conversion's scale
+// operand contributes a power of two only (it uses the exponent of its argument): 2^4 here, so that the product
+// with S_block * 2^-8 is a normal FP16 for every scale code; both factors and the product are exact.
 __device__ __forceinline__ half8_t expand8(uint32_t q, half2_t f)
 {
-    const half2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 1.0f, 0) * f;
-    const half2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 1.0f, 1) * f;
-    const half2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 1.0f, 2) * f;
-    const half2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 1.0f, 3) * f;
+    const half2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 16.0f, 0) * f;
+    const half2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 16.0f, 1) * f;
+    const half2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 16.0f, 2) * f;
+    const half2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q, 16.0f, 3) * f;
     half8_t r;
     r[0] = p0.x; r[1] = p0.y; r[2] = p1.x; r[3] = p1.y;
     r[4] = p2.x; r[5] = p2.y; r[6] = p3.x; r[7] = p3.y;
@@ -78,10 +78,70 @@ __device__ __forceinline__ void lds_dma4(const void *base, uint32_t off, uint32_
 
 __device__ __forceinline__ uint32_t pick(uint4 v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
+// Epilogue of both product kernels: outer scales, conversion, stores.
+// SWAP (bf16 output): a lane holds one output row (m = lane % 32) and, per 32 x 32 block, four runs of four consecutive
+// columns; otherwise lanes run along the columns and accumulator element e sits in row 8 * (e / 4) + 4 * (lane / 32) + e % 4.
+template <int TM, int TN, int OUT, bool SWAP>
+__device__ __forceinline__ void store_tile(float16_t (&acc)[TM][TN], const GemmArgs &g, int64_t m0, int64_t n0, int wm, int wn,
+                                           int lr, int kg)
+{
+    constexpr bool SPLIT = OUT == 2;
+    float alpha = 1.0f;
+    if (!SPLIT) alpha = g.a_gscale[0] * g.b_gscale[0] * 256.0f;
+    if (SWAP) {
+        // a lane holds one output row (m = lane % 32) and, per 32 x 32 block, four runs of four consecutive columns
+        // (n = 8 * (e / 4) + 4 * (lane / 32) + e % 4): each run leaves as one 8-byte store
+        uint16_t *outh = reinterpret_cast<uint16_t *>(g.out);
+        const bool vec = (g.N & 3) == 0;             // then every run is aligned and entirely inside or outside
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = m0 + (wm * TM + i) * 32 + lr;
+            if (m >= g.M) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t n = n0 + (wn * TN + j) * 32 + 8 * q + 4 * kg;
+                    const float v0 = acc[i][j][4 * q] * alpha, v1 = acc[i][j][4 * q + 1] * alpha;
+                    const float v2 = acc[i][j][4 * q + 2] * alpha, v3 = acc[i][j][4 * q + 3] * alpha;
+                    if (vec) {
+                        if (n < g.N) {
+                            const bf16x2_t lo = __builtin_convertvector((float2_t){v0, v1}, bf16x2_t);
+                            const bf16x2_t hi = __builtin_convertvector((float2_t){v2, v3}, bf16x2_t);
+                            *reinterpret_cast<uint2 *>(outh + m * g.N + n) =
+                                make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+                        }
+                    } else {
+                        const float v[4] = {v0, v1, v2, v3};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (n + t < g.N) outh[m * g.N + n + t] = (uint16_t)f32_to_bf16_bits(v[t]);
+                    }
+                }
+        }
+    } else {
+        // acc element e of a lane: row 8 * (e / 4) + 4 * (lane / 32) + e % 4, column lane % 32
+        float *outf = reinterpret_cast<float *>(g.out);
+        if (SPLIT) outf += (int64_t)blockIdx.z * g.M * g.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t n = n0 + (wn * TN + j) * 32 + lr;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * kg + (e & 3);
+                    if (m < g.M && n < g.N) outf[m * g.N + n] = acc[i][j][e] * alpha;
+                }
+            }
+    }
+}
+
 // Tile TM*64 x TN*64 per workgroup (2 x 2 waves, TM x TN MFMA tiles of 32 x 32 each), NC chunks of
 // 64 k per pipeline stage, three stage buffers in LDS.  Codes and scale bytes go global -> LDS
 // directly (a wave instruction fills 64 consecutive 16-byte / 4-byte slots), two stages ahead.
-//   codes : slot of (row, 16-byte piece p of the stage's row segment) = row * SLOTS + (p ^ swz(row))
+//   codes : slot of (row, 16-byte piece p of the stage's row segment) = row * SLOTS + (p ^ swz(row)), swz(row) =
+//           (row >> 2) % SLOTS: 16 consecutive rows then cover 16 different 16-byte columns of the 256-byte bank row
 //   scales: dword of (chunk c, row) = c * ROWS + row   (A rows first, then B rows); when K is a multiple of 256
 //           (PS = true) scale bytes are instead fetched 16 per row (four chunks = two stages) into a ring of
 //           three [ROWS][16] buffers, half of the rows per stage, four stages ahead: one 16-byte request per
@@ -171,7 +231,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
         for (int u = 0; u < LA + LB; ++u) {
             const bool isA = u < LA;
             const int slot = ((isA ? u : u - LA) * 4 + wave) * 64 + lane, row = slot / SLOTS, pos = slot % SLOTS;
-            const int piece = pos ^ ((row >> 1) & (SLOTS - 1));
+            const int piece = pos ^ ((row >> 2) & (SLOTS - 1));
             coff[u] = (uint32_t)row * (uint32_t)cstride + (uint32_t)piece * 16u;
             cpieces |= (uint32_t)piece << (4 * u);
             if ((isA ? m0 : n0) + row < (isA ? g.M : g.N)) rowmask |= 1u << u;
@@ -261,13 +321,13 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = (wm * TM + i) * 32 + lr;
-                r.qa[i] = codes[row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
+                r.qa[i] = codes[row * SLOTS + ((2 * c + kg) ^ ((row >> 2) & (SLOTS - 1)))];
                 if (!PS) scA[c][i] = scales[row];
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int row = (wn * TN + j) * 32 + lr;
-                r.qb[j] = codes[A_SLOTS + row * SLOTS + ((2 * c + kg) ^ ((row >> 1) & (SLOTS - 1)))];
+                r.qb[j] = codes[A_SLOTS + row * SLOTS + ((2 * c + kg) ^ ((row >> 2) & (SLOTS - 1)))];
                 if (!PS) scB[c][j] = scales[BM + row];
             }
             if (!PS) live[c] = is_live ? 0xFFu : 0u;
@@ -361,56 +421,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
         __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the look-ahead loads before the LDS is released
     }
 
-    constexpr bool SPLIT = OUT == 2;
-    float alpha = 1.0f;
-    if (!SPLIT) alpha = g.a_gscale[0] * g.b_gscale[0] * 256.0f;
-    if (SWAP) {
-        // a lane holds one output row (m = lane % 32) and, per 32 x 32 block, four runs of four consecutive columns
-        // (n = 8 * (e / 4) + 4 * (lane / 32) + e % 4): each run leaves as one 8-byte store
-        uint16_t *outh = reinterpret_cast<uint16_t *>(g.out);
-        const bool vec = (g.N & 3) == 0;             // then every run is aligned and entirely inside or outside
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int64_t m = m0 + (wm * TM + i) * 32 + lr;
-            if (m >= g.M) continue;
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t n = n0 + (wn * TN + j) * 32 + 8 * q + 4 * kg;
-                    const float v0 = acc[i][j][4 * q] * alpha, v1 = acc[i][j][4 * q + 1] * alpha;
-                    const float v2 = acc[i][j][4 * q + 2] * alpha, v3 = acc[i][j][4 * q + 3] * alpha;
-                    if (vec) {
-                        if (n < g.N) {
-                            const bf16x2_t lo = __builtin_convertvector((float2_t){v0, v1}, bf16x2_t);
-                            const bf16x2_t hi = __builtin_convertvector((float2_t){v2, v3}, bf16x2_t);
-                            *reinterpret_cast<uint2 *>(outh + m * g.N + n) =
-                                make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
-                        }
-                    } else {
-                        const float v[4] = {v0, v1, v2, v3};
-#pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            if (n + t < g.N) outh[m * g.N + n + t] = (uint16_t)f32_to_bf16_bits(v[t]);
-                    }
-                }
-        }
-    } else {
-        // acc element e of a lane: row 8 * (e / 4) + 4 * (lane / 32) + e % 4, column lane % 32
-        float *outf = reinterpret_cast<float *>(g.out);
-        if (SPLIT) outf += (int64_t)blockIdx.z * g.M * g.N;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int64_t n = n0 + (wn * TN + j) * 32 + lr;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * kg + (e & 3);
-                    if (m < g.M && n < g.N) outf[m * g.N + n] = acc[i][j][e] * alpha;
-                }
-            }
-    }
+    store_tile<TM, TN, OUT, SWAP>(acc, g, m0, n0, wm, wn, lr, kg);
 }
 
 // sum the split-K partials in split order, scale, convert
