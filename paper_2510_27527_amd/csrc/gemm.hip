@@ -12,6 +12,11 @@
 // of its row (one 128-bit LDS read) and uses 8 of them per MFMA; A and B use the same assignment,
 // so the order of k inside a chunk does not matter.  Small outputs with a long reduction (the
 // weight gradient) are split along K into FP32 partials that a second kernel sums in a fixed order.
+#ifdef TJ_DEV_FORCE
+#include <stdio.h>
+#include <stdlib.h>
+#endif
+
 #include "device_fmt.h"
 #include "internal.h"
 
@@ -179,7 +184,8 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
     constexpr bool SWAP = OUT == 0;
     static_assert(!PS || NC == 2, "paired scale fetch assumes two chunks per stage");
     static_assert(NC % 2 == 0, "chunk parity must repeat per stage");
-    static_assert(LA >= 1 && LB >= 1 && (PS || LS >= 1) && (ROWS * NC) % kThreads == 0, "tile too small");
+    static_assert(LA >= 1 && LB >= 1 && A_SLOTS % kThreads == 0 && B_SLOTS % kThreads == 0, "tile too small");
+    static_assert(PS || (LS >= 1 && (ROWS * NC) % kThreads == 0), "per-chunk scale fetch needs whole instructions");
     static_assert(NLOAD <= 15, "vmcnt immediate below assumes at most 15 loads per stage");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
@@ -464,7 +470,9 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *__
 // the tile and the number of K splits for a problem.
 struct TileCfg { int tm, tn; double t_stage; double t_fixed; int occupancy; };
 // t_stage: one 128-k pipeline stage of one workgroup with the CU to itself; t_fixed: prologue + epilogue
-const TileCfg kTiles[] = {{4, 4, 3.2, 6.0, 1}, {4, 2, 2.0, 5.0, 1}, {2, 4, 2.0, 5.0, 1}, {2, 2, 1.5, 5.0, 3}};
+// the 128 x 192 tile exists for the paired scale fetch only (K a multiple of 256)
+const TileCfg kTiles[] = {{4, 4, 3.2, 6.0, 1}, {4, 2, 2.0, 5.0, 1}, {2, 4, 2.0, 5.0, 1}, {2, 2, 1.5, 5.0, 3}, {2, 3, 1.4, 5.0, 2}};
+constexpr int kNumTiles = 5;
 constexpr int kNumCU = 256;
 constexpr int kNC = 2;
 
@@ -475,11 +483,22 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
     const int64_t chunks = K / 64;
     Plan best{3, 1, (int)chunks};
     double best_t = 1e300;
-    for (int t = 0; t < 4; ++t) {
+#ifdef TJ_DEV_FORCE
+    int force_tile = -1, force_split = 0;
+    if (const char *f = getenv("TJ_FORCE")) sscanf(f, "%d,%d", &force_tile, &force_split);
+#endif
+    for (int t = 0; t < kNumTiles; ++t) {
+        if (t == 4 && K % 256 != 0) continue;
+#ifdef TJ_DEV_FORCE
+        if (force_tile >= 0 && t != force_tile) continue;
+#endif
         const int64_t bm = 64 * kTiles[t].tm, bn = 64 * kTiles[t].tn;
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         for (int split = 1; split <= 16; ++split) {
             if (split > 1 && chunks / split < 8) break;
+#ifdef TJ_DEV_FORCE
+            if (force_split > 0 && split != force_split) continue;
+#endif
             int64_t cps = (chunks + split - 1) / split;
             if (chunks % 4 == 0) cps = (cps + 3) / 4 * 4;                       // splits on 256-k boundaries
             if (split > 1 && (chunks + cps - 1) / cps != split) continue;      // same launch as a smaller split
@@ -523,6 +542,9 @@ hipError_t launch_tile(int tile, const GemmArgs &g, dim3 grid, hipStream_t st)
         case 0: return launch_cfg<4, 4, OUT, PS>(g, grid, st);
         case 1: return launch_cfg<4, 2, OUT, PS>(g, grid, st);
         case 2: return launch_cfg<2, 4, OUT, PS>(g, grid, st);
+        case 4:
+            if constexpr (PS) return launch_cfg<2, 3, OUT, true>(g, grid, st);
+            else return hipErrorInvalidValue;
         default: return launch_cfg<2, 2, OUT, PS>(g, grid, st);
     }
 }
