@@ -9,8 +9,11 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtjnvfp4.so")
-SOURCES = ["api.hip", "quant.hip", "gemm.hip"]
-HEADERS = ["device_fmt.h", "internal.h", os.path.join("..", "..", "include", "tjnvfp4.h")]
+# (source, object name, extra flags): the product kernel's instantiations are compiled in six slices, in parallel
+SOURCES = [("api.hip", "api.o", []), ("quant.hip", "quant.o", []), ("gemm.hip", "gemm.o", [])] + [
+    ("gemm_inst.hip", "gemm_inst_ps%d_out%d.o" % (ps, out), ["-DTJ_GEMM_PS=%d" % ps, "-DTJ_GEMM_OUT=%d" % out])
+    for ps in (1, 0) for out in (0, 2, 1)]
+HEADERS = ["device_fmt.h", "internal.h", "gemm_args.h", "gemm_kernel.h", os.path.join("..", "..", "include", "tjnvfp4.h")]
 
 # -ffp-contract=off: the quantizer arithmetic is one IEEE rounding per written operation.
 # packed-fp32-ops is switched off: hipcc then never forms v_pk_{add,mul,fma}_f32 on its own.
@@ -33,15 +36,15 @@ def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
     headers = [os.path.join(CSRC, h) for h in HEADERS]
     jobs = []
-    for s in SOURCES:
+    for s, o, extra in SOURCES:
         src = os.path.join(CSRC, s)
-        obj = os.path.join(objdir, s.replace(".hip", ".o"))
+        obj = os.path.join(objdir, o)
         if force or _stale(obj, [src] + headers):
-            jobs.append((src, obj))
+            jobs.append((src, obj, extra))
 
     def compile_one(job):
-        src, obj = job
-        cmd = [hipcc] + FLAGS + ["-c", src, "-o", obj]
+        src, obj, extra = job
+        cmd = [hipcc] + FLAGS + extra + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
@@ -49,9 +52,10 @@ def build(force: bool = True, verbose: bool = False) -> str:
             sys.stderr.write(r.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(4, max(1, len(jobs)))) as ex:
+    workers = max(1, min(len(jobs), os.cpu_count() or 4, 8))
+    with ThreadPoolExecutor(max_workers=workers) as ex:
         list(ex.map(compile_one, jobs))
-    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    objs = [os.path.join(objdir, o) for _, o, _ in SOURCES]
     if jobs or not os.path.exists(LIB):
         cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
         r = subprocess.run(cmd, capture_output=True, text=True)
