@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (reference point for HBM byte counters)")
+    ap.add_argument("--square-gemm", type=int, default=0, metavar="REPS",
+                    help="only run the 8192^3 product on pre-quantized operands REPS times (for counter profiles)")
     return ap.parse_args()
 
 
@@ -65,6 +67,24 @@ def main():
     B = tj.binding
     B.lib()
 
+    if args.square_gemm:
+        n = 8192
+        gen = torch.Generator(device=dev).manual_seed(0)
+        ops = []
+        for _ in range(2):
+            t = tj.alloc_nvfp4(n, n)
+            t.codes.copy_(torch.randint(0, 256, t.codes.shape, dtype=torch.uint8, device=dev, generator=gen))
+            t.scales.copy_(torch.randint(0x30, 0x40, t.scales.shape, dtype=torch.uint8, device=dev, generator=gen))
+            t.gscale.fill_(1.0)
+            ops.append(t)
+        out = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
+        ws = tj.alloc_workspace(16)
+        for _ in range(args.square_gemm):
+            tj.gemm_nt(ops[0], ops[1], B.OUT_BF16, out=out, ws=ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"square_gemm_launches": args.square_gemm, "flops_per_launch": 2.0 * n ** 3}))
+        return
+
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
 
@@ -82,6 +102,14 @@ def main():
         L["ws"] = tj.alloc_workspace(nbytes)
         layers.append(L)
     flops_step = wl.config_flops(args.workload)
+    # lower bound of a step from the two rooflines, per linear: bf16 reads of X, W, dY, packed operands written and
+    # read once each (Q1..Q6), bf16 writes of Y, dX, dW
+    t_min = 0.0
+    for L in layers:
+        N, D, C = L["N"], L["D"], L["C"]
+        nbytes = 2.0 * (N * D + C * D + N * C) + 2 * 0.5625 * (N * D + C * D) * 2 + 2 * 0.5625 * (2 * N * C) \
+            + 2.0 * (N * C + N * D + C * D)
+        t_min += max(3 * 2.0 * N * D * C / (MFMA_F16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9))
 
     def step(sr_seed):
         for L in layers:
@@ -149,6 +177,7 @@ def main():
                       "linears": [[L["name"], L["D"], L["C"]] for L in layers], "outer_scale": "per-tensor",
                       "flops_per_step": flops_step},
            "frac_of_mfma_peak": round(value / MFMA_F16_PEAK_TFLOPS, 4),
+           "frac_of_roofline_lower_bound": round(t_min * 1e3 / ms_per_step, 4),
            "roofline": roofline}
 
     if not args.no_extras:
@@ -190,7 +219,11 @@ def extras(tj, wl, np, torch, dev_bf16):
         "row_sr_amax_given": lambda i: tj.quantize(bufs[i % 4], 0, B.ROUND_SR, outs[i % 2], seed=7, amax_in=amax, ws=ws),
         "col_sr_amax_given": lambda i: tj.quantize(bufs[i % 4], 1, B.ROUND_SR, outs[i % 2], seed=7, amax_in=amax, ws=ws),
         "col_sr_with_amax_pass": lambda i: tj.quantize(bufs[i % 4], 1, B.ROUND_SR, outs[i % 2], seed=7, ws=ws),
+        # the paper's own outer scale (1 x 128 blocks) needs no maximum pass at all
+        "row_rtn_block128_single_pass": lambda i: tj.quantize(bufs[i % 4], 0, B.ROUND_RTN, outs128[i % 2],
+                                                              outer=B.OUTER_BLOCK128, ws=ws),
     }
+    outs128 = [tj.alloc_nvfp4(R, Cc, B.OUTER_BLOCK128) for _ in range(2)]
     for name, fn in cases.items():
         for i in range(300):                           # long enough for the clocks to settle
             fn(i)
@@ -198,6 +231,16 @@ def extras(tj, wl, np, torch, dev_bf16):
         ms = time_events(torch, fn, 200)
         gbs = alg_bytes / (ms * 1e-3) / 1e9
         res["quant_8192x8192_" + name] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    # both backward operands of one tensor from a single read: 2 B in + 2 x 0.5625 B out per element
+    fn = lambda i: tj.quantize_dual(bufs[i % 4], B.ROUND_SR, outs[0], outs[1], seed=7, tensor_id_row=3, tensor_id_col=5,
+                                    amax_in=amax, ws=ws)
+    for i in range(300):
+        fn(i)
+    torch.cuda.synchronize()
+    ms = time_events(torch, fn, 200)
+    gbs = (R * Cc * 2 + 2 * (R * Cc // 2 + R * Cc // 16) + 8) / (ms * 1e-3) / 1e9
+    res["quant_8192x8192_dual_row_col_sr_amax_given"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1),
+                                                          "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
     # re-quantization of a packed tensor (Q4 / Q6): 0.5625 B in + 0.5625 B out per element
     src = outs[0]
     tj.quantize(bufs[0], 0, B.ROUND_RTN, src, ws=ws)

@@ -100,6 +100,16 @@ int nvfp4_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis
                    const nvfp4_qcfg *cfg, nvfp4_tensor *out, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Both backward operands of one bf16 [R x C] tensor from a single read of it (Sec. 2.3: Q3 and Q5 both act on dY):
+ * out_row describes [R x C] grouped along C (what axis 0 of nvfp4_quantize gives, stream id cfg->tensor_id), out_col
+ * the transpose [C x R] grouped along R (axis 1, stream id tensor_id_col).  Rounding, scale rounding, seed and
+ * maximum are cfg's and shared; TENSOR outer mode only; R and C multiples of 16.  Every byte equals that of the two
+ * separate calls.  ws as for nvfp4_quantize (needed when cfg->amax_in is NULL).
+ */
+int nvfp4_quantize_dual(const void *src, int64_t R, int64_t C, const nvfp4_qcfg *cfg, uint32_t tensor_id_col,
+                        nvfp4_tensor *out_row, nvfp4_tensor *out_col, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Out[M x N] = A[M x K] * B[N x K]^T on two quantized operands grouped along K (Sec. 2.3: all three products take
  * this form).  Products of dequantized 16-bit values are exact; accumulation is FP32; the outer scales multiply
  * the accumulator at the end; Out is row-major bf16 or f32.  Both operands must be in TENSOR outer mode.

@@ -24,7 +24,7 @@ SRC_BF16, SRC_NVFP4 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW, OP_LINEAR_BWD = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ["nvfp4_quantize", "nvfp4_gemm_nt", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd",
+EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd",
            "nvfp4_workspace_bytes", "nvfp4_gemm_plan", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
 
 
@@ -57,6 +57,9 @@ def lib():
         vp, i64, i32, u64, u32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_uint32, C.c_size_t
         L.nvfp4_quantize.restype = i32
         L.nvfp4_quantize.argtypes = [vp, i32, i64, i64, i32, C.POINTER(CQcfg), C.POINTER(CTensor), vp, sz, vp]
+        L.nvfp4_quantize_dual.restype = i32
+        L.nvfp4_quantize_dual.argtypes = [vp, i64, i64, C.POINTER(CQcfg), u32, C.POINTER(CTensor), C.POINTER(CTensor), vp, sz,
+                                          vp]
         L.nvfp4_gemm_nt.restype = i32
         L.nvfp4_gemm_nt.argtypes = [C.POINTER(CTensor), C.POINTER(CTensor), vp, i32, vp, sz, vp]
         L.nvfp4_linear_fwd.restype = i32
@@ -173,6 +176,30 @@ def quantize(src, axis: int, rounding: int, out: Optional[NVFP4Tensor] = None, *
     _check(rc, "nvfp4_quantize")
     out.rows, out.K, out.outer = co.rows, co.K, co.outer_mode
     return out
+
+
+def quantize_dual(src: torch.Tensor, rounding: int, out_row: Optional[NVFP4Tensor] = None,
+                  out_col: Optional[NVFP4Tensor] = None, *, scale_round: int = SCALE_DEFAULT, seed: int = 0,
+                  tensor_id_row: int = 0, tensor_id_col: int = 0, amax_in: Optional[torch.Tensor] = None,
+                  ws: Optional[torch.Tensor] = None):
+    """nvfp4_quantize_dual: row-wise [R, C] and column-wise [C, R] operands of a bf16 [R, C] tensor from one read."""
+    assert src.dtype == torch.bfloat16 and src.dim() == 2 and src.is_contiguous()
+    R, Cc = src.shape
+    dev = src.device
+    if out_row is None:
+        out_row = alloc_nvfp4(R, Cc, OUTER_TENSOR, dev)
+    if out_col is None:
+        out_col = alloc_nvfp4(Cc, R, OUTER_TENSOR, dev)
+    if ws is None:
+        ws = alloc_workspace(workspace_bytes(OP_QUANTIZE, R, Cc, 0, OUTER_TENSOR), dev)
+    cfg = CQcfg(rounding, scale_round, OUTER_TENSOR, tensor_id_row, seed, _ptr(amax_in))
+    cr, cc = out_row.c_struct(), out_col.c_struct()
+    rc = lib().nvfp4_quantize_dual(_ptr(src), R, Cc, C.byref(cfg), tensor_id_col, C.byref(cr), C.byref(cc), _ptr(ws),
+                                   ws.numel(), _stream())
+    _check(rc, "nvfp4_quantize_dual")
+    out_row.rows, out_row.K, out_row.outer = cr.rows, cr.K, cr.outer_mode
+    out_col.rows, out_col.K, out_col.outer = cc.rows, cc.K, cc.outer_mode
+    return out_row, out_col
 
 
 def _out_tensor(M, N, out_dtype, device):

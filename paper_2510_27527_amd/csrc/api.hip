@@ -348,6 +348,37 @@ int nvfp4_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis
     return run_quantize(src, pl, cfg, out, static_cast<float *>(ws), static_cast<hipStream_t>(stream));
 }
 
+int nvfp4_quantize_dual(const void *src, int64_t R, int64_t C, const nvfp4_qcfg *cfg, uint32_t tensor_id_col,
+                        nvfp4_tensor *out_row, nvfp4_tensor *out_col, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!cfg) return NVFP4_ERR_NULL;
+    if (cfg->outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;
+    nvfp4_qcfg ccol = *cfg;
+    ccol.tensor_id = tensor_id_col;
+    QuantPlan prow{}, pcol{};
+    int rc = plan_quantize(src, NVFP4_SRC_BF16, R, C, 0, cfg, out_row, &prow);
+    if (rc) return rc;
+    rc = plan_quantize(src, NVFP4_SRC_BF16, R, C, 1, &ccol, out_col, &pcol);
+    if (rc) return rc;
+    if (prow.need_partials && (!ws || ws_bytes < partials_bytes())) return NVFP4_ERR_WORKSPACE;
+    if (ws && !aligned16(ws)) return NVFP4_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    stamp(out_row, prow);
+    stamp(out_col, pcol);
+    if (R == 0 || C == 0) return NVFP4_OK;
+    QuantParams pr = params_of(prow, cfg), pc = params_of(pcol, &ccol);
+    if (cfg->amax_in) {
+        pr.amax_scalar = pc.amax_scalar = cfg->amax_in;
+    } else {
+        pr.npart = pc.npart = launch_amax_partials(src, R * C, static_cast<float *>(ws), nullptr, st);
+        pr.amax_partials = pc.amax_partials = static_cast<float *>(ws);
+    }
+    // the dequantized maximum is only produced by the deterministic row-wise quantizer of nvfp4_quantize
+    QuantOut orow{out_row->codes, out_row->scales, out_row->gscale, nullptr};
+    QuantOut ocol{out_col->codes, out_col->scales, out_col->gscale, nullptr};
+    return launch_quant_dual_bf16(src, R, C, pr, orow, pc, ocol, st) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
 int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *ws, size_t ws_bytes,
                   void *stream)
 {

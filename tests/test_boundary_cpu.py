@@ -80,6 +80,26 @@ def test_quantize_rejects_bad_arguments(lib):
     assert call(src, 32, 64, 0) == -3                     # same-axis re-quantization is not provided
 
 
+def test_quantize_dual_rejects_bad_arguments(lib):
+    cfg = B.CQcfg(1, 0, 0, 3, 0, None)
+
+    def call(src=FAKE, R=32, Cc=64, cfg=cfg, orow=None, ocol=None, ws=FAKE, ws_bytes=1 << 20):
+        orow = _tensor() if orow is None else orow
+        ocol = _tensor() if ocol is None else ocol
+        return lib.nvfp4_quantize_dual(src, R, Cc, C.byref(cfg) if cfg is not None else None, 5, C.byref(orow),
+                                       C.byref(ocol), ws, ws_bytes, None)
+    assert call(src=None) == -1
+    assert call(cfg=None) == -1
+    assert call(ocol=B.CTensor(None, FAKE, FAKE, None, 0, 0, 0, 0)) == -1
+    assert call(R=24) == -2                               # groups of 16 down the columns
+    assert call(Cc=24) == -2                              # groups of 16 along the rows
+    assert call(cfg=B.CQcfg(1, 0, 1, 3, 0, None)) == -3   # tensor mode only
+    assert call(cfg=B.CQcfg(5, 0, 0, 3, 0, None)) == -3
+    assert call(ws=None) == -4
+    assert call(ws_bytes=8) == -4
+    assert call(src=FAKE + 2) == -5
+
+
 def test_gemm_and_linear_reject_bad_arguments(lib):
     A, Bt = _tensor(128, 256), _tensor(64, 256)
     g = lambda a, b, out=FAKE, dt=0, ws=FAKE, wsb=1 << 30: lib.nvfp4_gemm_nt(C.byref(a), C.byref(b), out, dt, ws, wsb, None)

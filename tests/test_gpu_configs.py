@@ -123,6 +123,10 @@ def test_quantizer_stress_full():
     say("[cfg4] column-wise stochastic")
     same_bytes(tj.quantize(x, 1, B.ROUND_SR, seed=7, tensor_id=5),
                oracle.quantize_bf16(bits, 1, oracle.SR, seed=7, tensor_id=5), "col SR")
+    say("[cfg4] row-wise + column-wise stochastic from one read")
+    row, col = tj.quantize_dual(x, B.ROUND_SR, seed=7, tensor_id_row=3, tensor_id_col=5)
+    same_bytes(row, oracle.quantize_bf16(bits, 0, oracle.SR, seed=7, tensor_id=3), "dual row SR")
+    same_bytes(col, oracle.quantize_bf16(bits, 1, oracle.SR, seed=7, tensor_id=5), "dual col SR")
     say("[cfg4] row-wise stochastic, 1 x 128 outer blocks")
     same_bytes(tj.quantize(x, 0, B.ROUND_SR, seed=7, tensor_id=3, outer=B.OUTER_BLOCK128),
                oracle.quantize_bf16(bits, 0, oracle.SR, seed=7, tensor_id=3, outer=oracle.OUTER_BLOCK128), "row SR block128")

@@ -170,6 +170,23 @@ def test_quant_col(shape, rounding):
     assert_same(got, ref, "col %s r%d" % (shape, rounding))
 
 
+@pytest.mark.parametrize("shape", [(256, 512), (16, 16), (144, 80), (1040, 144), (272, 1024), (528, 2064)])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_quantize_dual_equals_both_quantizations(shape, rounding):
+    """One read of the tensor, both backward operands: the bytes of the row-wise and of the column-wise call."""
+    bits = wl.normal_bf16(shape, 1e-3, 31)
+    x = dev_bf16(bits)
+    row, col = tj.quantize_dual(x, rounding, seed=9, tensor_id_row=11, tensor_id_col=13)
+    assert_same(row, oracle.quantize_bf16(bits, 0, rounding, scale_round=2 if rounding else 1, seed=9, tensor_id=11), "dual row")
+    assert_same(col, oracle.quantize_bf16(bits, 1, rounding, scale_round=2 if rounding else 1, seed=9, tensor_id=13), "dual col")
+    # with the maximum supplied by the caller
+    amax = tj.amax_bf16(x, tj.alloc_workspace(1 << 14))
+    row2, col2 = tj.quantize_dual(x, rounding, seed=9, tensor_id_row=11, tensor_id_col=13, amax_in=amax)
+    torch.cuda.synchronize()
+    assert torch.equal(row2.codes, row.codes) and torch.equal(col2.codes, col.codes)
+    assert torch.equal(row2.scales, row.scales) and torch.equal(col2.scales, col.scales)
+
+
 @pytest.mark.parametrize("shape", [(256, 512), (16, 16), (144, 80), (1040, 144), (272, 1024)])
 @pytest.mark.parametrize("rounding", [0, 1])
 def test_requant_col(shape, rounding):
