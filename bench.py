@@ -219,11 +219,14 @@ def extras(tj, wl, np, torch, dev_bf16):
         "row_sr_amax_given": lambda i: tj.quantize(bufs[i % 4], 0, B.ROUND_SR, outs[i % 2], seed=7, amax_in=amax, ws=ws),
         "col_sr_amax_given": lambda i: tj.quantize(bufs[i % 4], 1, B.ROUND_SR, outs[i % 2], seed=7, amax_in=amax, ws=ws),
         "col_sr_with_amax_pass": lambda i: tj.quantize(bufs[i % 4], 1, B.ROUND_SR, outs[i % 2], seed=7, ws=ws),
-        # the paper's own outer scale (1 x 128 blocks) needs no maximum pass at all
+        # the paper's own outer scale (1 x 128 blocks) needs no maximum pass at all (the optional dequantized maximum,
+        # which only a later tensor-mode re-quantization would use, is not requested)
         "row_rtn_block128_single_pass": lambda i: tj.quantize(bufs[i % 4], 0, B.ROUND_RTN, outs128[i % 2],
                                                               outer=B.OUTER_BLOCK128, ws=ws),
+        "row_sr_block128_single_pass": lambda i: tj.quantize(bufs[i % 4], 0, B.ROUND_SR, outs128[i % 2], seed=7,
+                                                             outer=B.OUTER_BLOCK128, ws=ws),
     }
-    outs128 = [tj.alloc_nvfp4(R, Cc, B.OUTER_BLOCK128) for _ in range(2)]
+    outs128 = [tj.alloc_nvfp4(R, Cc, B.OUTER_BLOCK128, with_amax=False) for _ in range(2)]
     for name, fn in cases.items():
         for i in range(300):                           # long enough for the clocks to settle
             fn(i)
