@@ -216,6 +216,26 @@ def test_gemm_nt(M, N, K, out_dtype):
     check_product(got, ref, absref, "gemm %dx%dx%d" % (M, N, K))
 
 
+@pytest.mark.parametrize("M,N,K", [(8100, 700, 768), (8155, 745, 768), (3000, 770, 2304), (700, 760, 8192),
+                                   (8192, 2000, 768), (1000, 520, 3072)])
+@pytest.mark.parametrize("out_dtype", [0, 1])
+def test_gemm_ragged_large_tiles_sampled_rows(M, N, K, out_dtype):
+    """Shapes for which the planner takes its large workgroup tiles (128 x 192, 256 x 256, 256 x 128; with and without a
+    K split), with ragged edges in both directions and N not a multiple of 4: sampled rows, all columns."""
+    assert max(tj.binding.gemm_plan(M, N, K)[:2]) >= 192
+    A = oracle.quantize_bf16(wl.normal_bf16((M, K), 1.0, 700 + N, 1e-2, 50.0), 0, 0)
+    B = oracle.quantize_bf16(wl.normal_bf16((N, K), 0.02, 701 + M), 0, 1, seed=4)
+    got = tj.gemm_nt(to_dev(A), to_dev(B), out_dtype)
+    again = tj.gemm_nt(to_dev(A), to_dev(B), out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)                            # fixed summation order, also when K is split
+    rng = np.random.default_rng(M + N)
+    rows = np.unique(np.concatenate([[0, M - 1, (M // 128) * 128 - 1, (M // 128) * 128 % M],
+                                     rng.choice(M, 40, replace=False)]))
+    ref, absref = oracle.gemm_nt(A, B, rows_a=rows)
+    check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm %dx%dx%d" % (M, N, K))
+
+
 def test_gemm_exact_on_integer_operands():
     """Scales 1 and grid-valued operands: the product is a small-integer matrix product, exact in FP32."""
     rng = np.random.default_rng(7)
