@@ -285,20 +285,23 @@ struct ColArgs {
 // dword column of the tile, rotated by 4 per 16 rows
 __device__ __forceinline__ int tile_pos(int row, int dwcol) { return row * 32 + ((dwcol + 4 * (row >> 4)) & 31); }
 
-// 16 packed codes of one source group times its scale, as 8 dwords of bf16 pairs (exact)
+// 16 packed codes of one source group times its scale, as 8 dwords of bf16 pairs (exact: 6 significant bits).
+// The hardware conversion turns a byte into two binary32 values (signed zeros included); the product with the scale
+// is exact, and its upper half is the bf16 value.
 __device__ __forceinline__ void decode_group_bf16(uint2 codes, uint32_t sc, uint32_t (&out)[8])
 {
     const float sb = e4m3_value(sc);
-    const uint32_t w[2] = {codes.x, codes.y};
+    const float2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 0) * sb;
+    const float2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 1) * sb;
+    const float2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 2) * sb;
+    const float2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 3) * sb;
+    const float2_t p4 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 0) * sb;
+    const float2_t p5 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 1) * sb;
+    const float2_t p6 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 2) * sb;
+    const float2_t p7 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 3) * sb;
+    const float2_t p[8] = {p0, p1, p2, p3, p4, p5, p6, p7};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t byte = (w[i >> 2] >> (8 * (i & 3))) & 0xFFu;
-        const float lo = e2m1_value(byte & 7u) * sb;
-        const float hi = e2m1_value((byte >> 4) & 7u) * sb;
-        const uint32_t lob = (f2u(lo) >> 16) | ((byte & 8u) << 12);
-        const uint32_t hib = (f2u(hi) & 0xFFFF0000u) | ((byte & 0x80u) << 24);
-        out[i] = lob | hib;
-    }
+    for (int i = 0; i < 8; ++i) out[i] = __builtin_amdgcn_perm(f2u(p[i].y), f2u(p[i].x), 0x07060302u);
 }
 
 // what one thread brings in for one tile
@@ -341,7 +344,8 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
         const uint32_t per_xcd = gx * gy / 8;
         if (lin < per_xcd * 8) lin = (lin & 7) * per_xcd + (lin >> 3);
     }
-    const uint32_t by = lin / gx, bx = lin - by * gx;
+    // workgroup-uniform: keep them (and everything derived from them) in scalar registers
+    const uint32_t by = __builtin_amdgcn_readfirstlane(lin / gx), bx = __builtin_amdgcn_readfirstlane(lin % gx);
     const int64_t C0 = (int64_t)bx * kTileC;
     const uint32_t rt0 = by * (uint32_t)a.span;
     const int ntile = (int)min((uint32_t)a.span, tiles_r - rt0);
@@ -349,25 +353,28 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
     // ---- loads of one tile into registers (nothing here depends on the scale set-up)
     const int64_t ld_row = PACKED ? (tid >> 1) : (tid >> 3);
     const int64_t ld_col = C0 + (PACKED ? 32 * (tid & 1) : 8 * (tid & 7));
+    // element index of the thread's first load: its own part once, the tile's (workgroup-uniform) part per tile
+    const int64_t ld_lane = ld_row * C + ld_col;
     auto fetch = [&](int t, ColFetch<PACKED> &f) {
         const int64_t R0 = (int64_t)(rt0 + t) * kTileR;
         if constexpr (!PACKED) {
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
-                const int64_t gr = R0 + pass * 32 + ld_row;
+                const int64_t r_uni = R0 + pass * 32;                       // uniform
                 f.v[pass] = make_uint4(0, 0, 0, 0);
-                if (gr < R && ld_col < C) f.v[pass] = ld_stream(a.src + ((gr * C + ld_col) >> 3));
+                if (r_uni + ld_row < R && ld_col < C) f.v[pass] = ld_stream(a.src + ((r_uni * C + ld_lane) >> 3));
             }
         } else {
-            const int64_t gr = R0 + ld_row;
+            const int64_t e_uni = R0 * C;                                   // uniform
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 const int64_t gc = ld_col + 16 * b;
                 f.cw[b] = make_uint2(0, 0);
                 f.sc[b] = 0;
-                if (gr < R && gc < C) {
-                    f.cw[b] = *reinterpret_cast<const uint2 *>(a.src_codes + ((gr * C + gc) >> 1));
-                    f.sc[b] = a.src_scales[(gr * C + gc) >> 4];
+                if (R0 + ld_row < R && gc < C) {
+                    const int64_t e = e_uni + ld_lane + 16 * b;
+                    f.cw[b] = *reinterpret_cast<const uint2 *>(a.src_codes + (e >> 1));
+                    f.sc[b] = a.src_scales[e >> 4];
                 }
             }
         }
@@ -423,7 +430,7 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
                     const float r = os.inv_sg * inv_tab[sc];
                     const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
                                         bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-                    const int64_t e0 = gr * C + ld_col;
+                    const int64_t e0 = (R0 + pass * 32) * C + ld_lane;
                     const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 2), a.krow.k0, a.krow.k1);
                     if (valid) a.krow.codes[e0 >> 3] = qd;
                     const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
@@ -454,21 +461,25 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
 
         // phase 2
         uint32_t w[16];
+        ushort2_t m2 = {0, 0};                                              // max |.| of the two columns, as bf16 bits
 #pragma unroll
-        for (int i = 0; i < 16; ++i) w[i] = tile[tile_pos(16 * rb + i, cp)];
+        for (int i = 0; i < 16; ++i) {
+            w[i] = tile[tile_pos(16 * rb + i, cp)];
+            m2 = __builtin_elementwise_max(m2, as_us2(w[i] & 0x7FFF7FFFu));
+        }
         if (R0 + 16 * rb >= R) continue;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if (c_first + j >= C) break;
             float x0[8], x1[8];
-            float m = 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 x0[i] = j == 0 ? bf16_lo(w[i]) : bf16_hi(w[i]);
                 x1[i] = j == 0 ? bf16_lo(w[8 + i]) : bf16_hi(w[8 + i]);
                 if (PACKED) { x0[i] = x0[i] * src_sg; x1[i] = x1[i] * src_sg; }
-                m = fmaxf(m, fmaxf(__builtin_fabsf(x0[i]), __builtin_fabsf(x1[i])));
             }
+            float m = u2f((uint32_t)(j == 0 ? m2.x : m2.y) << 16);
+            if (PACKED) m = m * src_sg;                                     // rounding is monotone: = max |x|
             const float s = m * os.inv_cg;
             const uint32_t sc = e4m3_round<SUP>(s);
             const float r = os.inv_sg * inv_tab[sc];
