@@ -158,6 +158,14 @@ int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nv
                 p.npart = launch_amax_partials(src, pl.R * pl.C, partials, o.amax_deq, st);
                 p.amax_partials = partials;
                 zeroed = true;
+                if (pl.axis == 1 && pl.R * pl.C >= ((int64_t)1 << 23)) {
+                    // many small workgroups follow: one more tiny launch is cheaper than each of them reducing the
+                    // partials (the result may overwrite the first partial: it is written after all are read)
+                    launch_amax_final(partials, p.npart, partials, st);
+                    p.amax_scalar = partials;
+                    p.amax_partials = nullptr;
+                    p.npart = 0;
+                }
             }
         }
         if (!zeroed) launch_zero_scalar(o.amax_deq, st);

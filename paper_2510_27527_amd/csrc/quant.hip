@@ -151,8 +151,8 @@ __global__ __launch_bounds__(kThreads) void amax_partials_kernel(AmaxJob j0, Ama
     if (threadIdx.x == 0) partials[bid] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-__global__ __launch_bounds__(kThreads) void amax_final_kernel(const float *__restrict__ partials, int npart,
-                                                              float *__restrict__ out)
+// out may alias partials: it is written after every partial has been read
+__global__ __launch_bounds__(kThreads) void amax_final_kernel(const float *partials, int npart, float *out)
 {
     __shared__ float red[4];
     float m = 0.0f;
@@ -494,13 +494,13 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
     }
 }
 
-// number of workgroups of a column job (and its span): enough workgroups to fill the chip before a workgroup takes
-// several tiles
+// number of workgroups of a column job (and its span): a workgroup takes several tiles only when there are more than
+// 8192 tiles (measured: with fewer workgroups than that the chip is not kept busy)
 inline unsigned col_grid(ColArgs &a)
 {
     const int64_t tiles_c = (a.C + kTileC - 1) / kTileC, tiles_r = (a.R + kTileR - 1) / kTileR;
     int span = 4;
-    while (span > 1 && tiles_c * ((tiles_r + span - 1) / span) < 2048) span >>= 1;
+    while (span > 1 && tiles_c * ((tiles_r + span - 1) / span) < 8192) span >>= 1;
     a.span = span;
     return (unsigned)(tiles_c * ((tiles_r + span - 1) / span));
 }
