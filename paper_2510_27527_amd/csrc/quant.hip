@@ -17,27 +17,15 @@ namespace tj {
 namespace {
 
 constexpr int kThreads = 256;
-#ifndef TJ_ROW_ITER
-#define TJ_ROW_ITER 4
-#endif
-constexpr int kRowIter = TJ_ROW_ITER;    // 128-bit chunks per thread in the row kernel
+constexpr int kRowIter = 4;    // 128-bit chunks per thread in the row kernel
 
 // 128-bit load of source data that this kernel reads exactly once (streaming hint: the line need not stay cached)
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 ld_stream(const uint4 *p)
 {
-#ifndef TJ_NO_NT_LD
     const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
-#else
-    return *p;
-#endif
 }
-#ifdef TJ_NT_ST
-__device__ __forceinline__ void st_stream(uint32_t *p, uint32_t v) { __builtin_nontemporal_store(v, p); }
-#else
-__device__ __forceinline__ void st_stream(uint32_t *p, uint32_t v) { *p = v; }
-#endif
 
 struct KArgs {
     uint32_t *codes;
@@ -237,13 +225,13 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(RowJob j0, RowJob j
             const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
                                 bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
             const uint32_t q = quant8<ROUND, SUP>(x, r, (uint32_t)(c * 2), a.k0, a.k1);
-            if (valid) st_stream(a.codes + c, q);
+            if (valid) a.codes[c] = q;
             // four scale bytes (lanes c, c+2, c+4, c+6) travel to the lane with c % 8 == 0
             const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
             const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
             if (valid && (tid & 7) == 0) {
                 if (!CHECK || c + 8 <= nchunks) {
-                    st_stream(reinterpret_cast<uint32_t *>(a.scales) + (c >> 3), s4);
+                    reinterpret_cast<uint32_t *>(a.scales)[c >> 3] = s4;
                 } else {
                     for (int b = 0; b < 4; ++b)
                         if (c + 2 * b < nchunks) a.scales[(c >> 1) + b] = (uint8_t)(s4 >> (8 * b));

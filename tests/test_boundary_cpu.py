@@ -155,3 +155,12 @@ def test_workspace_sizes(lib):
 def test_stream_key_is_a_function_of_seed_and_id(lib):
     ks = {lib.nvfp4_stream_key(s, t) for s in range(8) for t in range(8)}
     assert len(ks) == 64
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message instead of measuring anything."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
