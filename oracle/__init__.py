@@ -63,6 +63,10 @@ def lib():
         L.oracle_global_scale.argtypes = [f32]
         L.oracle_quantize_rows.restype = i32
         L.oracle_quantize_rows.argtypes = [p, i64, i64, i32, i32, i32, u64, u32, p, p, p, p]
+        L.oracle_quantize_rows_y.restype = i32
+        L.oracle_quantize_rows_y.argtypes = [p, i64, i64, i32, i32, i32, u64, u32, p, p, p, p, p]
+        L.oracle_rand22_fill.restype = None
+        L.oracle_rand22_fill.argtypes = [u64, i64, p]
         L.oracle_dequant_f32.restype = i32
         L.oracle_dequant_f32.argtypes = [p, p, p, i64, i64, i32, p]
         L.oracle_dequant_f64.restype = i32

@@ -209,10 +209,10 @@ float oracle_global_scale(float amax)
  *   amax_deq (optional, [1]): max |binary32 dequantized value| of the result.
  * Returns 0, or -1 on a bad shape / enum.
  */
-int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
-                         int rounding, int scale_round, int outer_mode,
-                         uint64_t seed, uint32_t tensor_id,
-                         uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq)
+static int quantize_rows_impl(const float *x, int64_t rows, int64_t K,
+                              int rounding, int scale_round, int outer_mode,
+                              uint64_t seed, uint32_t tensor_id,
+                              uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq, float *y_out)
 {
     if (rows < 0 || K < 0 || K % 16) return -1;
     if (outer_mode == OUTER_BLOCK128 && K % 128) return -1;
@@ -259,6 +259,7 @@ int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
                 for (int i = 0; i < 16; ++i) {
                     int64_t k = b * 16 + i;
                     volatile float y = xb[i] * rcp;                    /* Sec. 2.2, argument of round_FP4 */
+                    if (y_out) y_out[r * K + k] = y;
                     float a = fabsf(y); if (a > 6.0f) a = 6.0f;
                     int m;
                     if (rounding == ROUND_RTN) m = oracle_round_rtn(a);
@@ -277,6 +278,31 @@ int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
     }
     if (amax_deq) *amax_deq = deq_max;
     return 0;
+}
+
+int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
+                         int rounding, int scale_round, int outer_mode,
+                         uint64_t seed, uint32_t tensor_id,
+                         uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq)
+{
+    return quantize_rows_impl(x, rows, K, rounding, scale_round, outer_mode, seed, tensor_id, codes, scales, gscale,
+                              amax_deq, NULL);
+}
+
+/* test helper: the same, and also the argument y of round_FP4 for every element ([rows][K]) */
+int oracle_quantize_rows_y(const float *x, int64_t rows, int64_t K,
+                           int rounding, int scale_round, int outer_mode,
+                           uint64_t seed, uint32_t tensor_id,
+                           uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq, float *y_out)
+{
+    return quantize_rows_impl(x, rows, K, rounding, scale_round, outer_mode, seed, tensor_id, codes, scales, gscale,
+                              amax_deq, y_out);
+}
+
+/* test helper: the 22 random bits of elements 0 .. n-1 of a stream */
+void oracle_rand22_fill(uint64_t key, int64_t n, uint32_t *out)
+{
+    for (int64_t e = 0; e < n; ++e) out[e] = oracle_rand22((uint64_t)e, key);
 }
 
 /* ----------------------------------------------------------- dequantizers -- */

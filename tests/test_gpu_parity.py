@@ -199,6 +199,14 @@ def test_requant_col(shape, rounding):
     assert_same(got, ref, "requant %s r%d" % (shape, rounding))
 
 
+def test_requant_on_the_truncation_boundary():
+    """Q6 of a 256 x 256 tensor with seed 1322: one argument below 1 sits exactly where dropping and rounding its bits
+    under 2^-23 give different codes (tests/test_oracle_pins.py shows that on the CPU); the GPU must drop them too."""
+    src = oracle.quantize_bf16(wl.normal_bf16((256, 256), 1.0, 77), 0, oracle.RTN)
+    got = tj.quantize(to_dev(src), 1, 1, seed=1322, tensor_id=6)
+    assert_same(got, oracle.requantize(src, 1, oracle.SR, seed=1322, tensor_id=6), "Q6 boundary case")
+
+
 # ------------------------------------------------------------------------ GEMM
 
 GEMM_SHAPES = [(128, 128, 64), (32, 32, 64), (200, 72, 192), (256, 384, 512), (130, 258, 1024), (64, 96, 4096),

@@ -470,3 +470,41 @@ def test_linear_layer_close_to_unquantized_and_aligned():
     eX_hat = np.abs(accX / n - Xhat.T).mean()
     eX_org = np.abs(accX / n - X.T).mean()
     assert eX_hat < 0.5 * eX_org
+
+
+def boundary_case():
+    """A small re-quantization (Q6 of a 256 x 256 tensor, seed 1322) in which one element sits exactly on the boundary
+    where dropping and rounding the bits below 2^-23 of an argument below 1 give different codes."""
+    import workloads as wl
+    Xb = wl.normal_bf16((256, 256), 1.0, 77)
+    src = oracle.quantize_bf16(Xb, 0, oracle.RTN)
+    return src, 1322, 6, 16083
+
+
+def test_sr_boundary_case_is_on_the_truncation_boundary():
+    """R5 below 1: the bits of the argument under 2^-23 are dropped.  In this case floor(a 2^23) + u = 2^22 - 1 (no carry:
+    the lower neighbour) while the dropped fraction is >= 1/2, so rounding to nearest first would have carried."""
+    L = oracle.lib()
+    src, seed, tid, e = boundary_case()
+    x = oracle.transpose_f32(oracle.dequant_f32(src))
+    rows, K = x.shape
+    codes = np.zeros((rows, K // 2), np.uint8)
+    scales = np.zeros((rows, K // 16), np.uint8)
+    gs = np.zeros(1, np.float32)
+    y = np.zeros((rows, K), np.float32)
+    rc = L.oracle_quantize_rows_y(oracle._ptr(x), rows, K, oracle.SR, 0, 0, seed, tid, oracle._ptr(codes), oracle._ptr(scales),
+                                  oracle._ptr(gs), None, oracle._ptr(y))
+    assert rc == 0
+    a = float(abs(y.ravel()[e]))
+    u = L.oracle_rand22(e, L.oracle_stream_key(seed, tid))
+    F = a * 2.0 ** 23
+    assert a < 1.0 and F - np.floor(F) >= 0.5
+    assert (int(np.floor(F)) & 0x3FFFFF) + u == (1 << 22) - 1
+    lower = L.oracle_round_sr(a, u)
+    assert L.oracle_round_sr(a, u + 1) == lower + 1          # one more and it carries
+    r, k = divmod(e, K)
+    nib = (codes[r, k // 2] >> (4 * (k & 1))) & 7
+    assert nib == lower
+    # the same call through the ordinary entry point gives the same bytes
+    ref = oracle.requantize(src, 1, oracle.SR, seed=seed, tensor_id=tid)
+    assert np.array_equal(ref.codes, codes) and np.array_equal(ref.scales, scales)
