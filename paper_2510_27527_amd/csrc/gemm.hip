@@ -15,6 +15,13 @@ namespace {
 constexpr int kThreads = kGemmThreads;
 constexpr int kNC = 2;
 
+// partials are read exactly once: streaming load
+__device__ __forceinline__ float4 ld4(const float *p)
+{
+    const float4_t v = __builtin_nontemporal_load(reinterpret_cast<const float4_t *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // sum the split-K partials in split order, scale, convert
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *__restrict__ part, int split,
                                                                  int64_t mn, const float *a_gscale,
@@ -24,9 +31,9 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *__
     const int64_t i4 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
     if (i4 >= mn) return;
     if ((mn & 3) == 0) {
-        float4 s = *reinterpret_cast<const float4 *>(part + i4);
+        float4 s = ld4(part + i4);
         for (int z = 1; z < split; ++z) {
-            const float4 t = *reinterpret_cast<const float4 *>(part + (int64_t)z * mn + i4);
+            const float4 t = ld4(part + (int64_t)z * mn + i4);
             s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
         }
         s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
