@@ -34,6 +34,10 @@
  *   gscale               FP32 outer scale(s): [1] (NVFP4_OUTER_TENSOR) or
  *                        [rows][K/128] (NVFP4_OUTER_BLOCK128)
  *   value(r,k) = E2M1(code) * E4M3(scales[r][k/16]) * gscale[...]
+ *
+ * Empty inputs (a size of 0) are accepted everywhere: nothing is launched for an empty tensor, an empty product is
+ * skipped, and a product over an empty reduction (K = 0) is written as zeros.  Device pointers of empty tensors are
+ * never dereferenced but must still be non-NULL and 16-byte aligned.
  */
 #ifndef TJNVFP4_H
 #define TJNVFP4_H

@@ -97,8 +97,20 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+_EMPTY = {}
+
+
 def _ptr(t: Optional[torch.Tensor]):
-    return None if t is None else t.data_ptr()
+    """Device address of a tensor.  An empty tensor has no storage; the library still wants a non-NULL, 16-byte
+    aligned pointer for it (it never dereferences it), so it gets the address of a small per-device placeholder."""
+    if t is None:
+        return None
+    if t.numel() == 0 and t.is_cuda:
+        key = t.device.index
+        if key not in _EMPTY:
+            _EMPTY[key] = torch.zeros(64, dtype=torch.uint8, device=t.device)
+        return _EMPTY[key].data_ptr()
+    return t.data_ptr()
 
 
 @dataclass

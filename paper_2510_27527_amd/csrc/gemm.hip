@@ -15,6 +15,13 @@ namespace {
 constexpr int kThreads = kGemmThreads;
 constexpr int kNC = 2;
 
+// K = 0: the product is all zeros (no operand, and no outer scale, is looked at)
+__global__ __launch_bounds__(kThreads) void zero_out_kernel(uint16_t *out, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) out[i] = 0;
+}
+
 // partials are read exactly once: streaming load
 __device__ __forceinline__ float4 ld4(const float *p)
 {
@@ -73,6 +80,7 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
 {
     const int64_t chunks = K / 64;
     Plan best{3, 1, (int)chunks};
+    if (M <= 0 || N <= 0 || chunks == 0) return best;      // nothing to tile (empty output or empty reduction)
     double best_t = 1e300;
 #ifdef TJ_DEV_FORCE
     int force_tile = -1, force_split = 0;
@@ -105,7 +113,6 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
             if (time < best_t) { best_t = time; best = Plan{t, split, (int)cps}; }
         }
     }
-    if (chunks == 0) best = Plan{3, 1, 0};
     return best;
 }
 
@@ -130,6 +137,13 @@ hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K,
 {
     const int64_t M = A.rows, N = B.rows;
     if (M == 0 || N == 0) return hipSuccess;
+    if (K == 0) {
+        const int64_t n16 = M * N * (out_f32 ? 2 : 1);
+        const int64_t want = (n16 + kThreads - 1) / kThreads;
+        hipLaunchKernelGGL(zero_out_kernel, dim3((unsigned)(want > 4096 ? 4096 : want)), dim3(kThreads), 0, st,
+                           static_cast<uint16_t *>(out), n16);
+        return hipGetLastError();
+    }
     Plan p = make_plan(M, N, K);
     if (p.split > 1 && (ws == nullptr || ws_bytes < (size_t)p.split * M * N * sizeof(float))) return hipErrorInvalidValue;
     GemmArgs g;

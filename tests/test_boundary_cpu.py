@@ -164,3 +164,15 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_planner_and_workspace_accept_empty_products(lib):
+    """An empty output or an empty reduction has nothing to tile: plan and workspace size come back without arithmetic
+    on a zero tile count (every linear-layer call sizes its workspace through this path)."""
+    for M, N, K in [(0, 64, 128), (64, 0, 128), (64, 128, 0), (0, 0, 0)]:
+        bm, bn, sp = C.c_int(), C.c_int(), C.c_int()
+        assert lib.nvfp4_gemm_plan(M, N, K, C.byref(bm), C.byref(bn), C.byref(sp)) == 0
+        assert sp.value == 1
+        assert lib.nvfp4_workspace_bytes(B.OP_GEMM, M, K, N, 0) == 0
+    for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD_DX, B.OP_LINEAR_BWD_DW, B.OP_LINEAR_BWD):
+        assert lib.nvfp4_workspace_bytes(op, 0, 128, 64, 0) > 0

@@ -368,3 +368,27 @@ def test_fused_backward_equals_separate_calls(N, D, C):
     oXq, oWq = oracle.linear_fwd(Xb, Wb)
     ref, absref = oracle.gemm_nt(*oracle.linear_bwd_dw_operands(dYb, oXq, 17, 3))
     check_product(dW2, ref, absref, "fused dW")
+
+
+# ------------------------------------------------------------------ degenerate sizes
+
+def test_empty_inputs_are_accepted_and_write_nothing():
+    """Zero rows / zero tokens: every entry point returns OK, launches nothing that could fault, leaves outputs alone."""
+    B = tj.binding
+    dev = torch.device("cuda")
+    x0 = torch.empty((0, 128), dtype=torch.bfloat16, device=dev)
+    q = tj.quantize(x0, 0, B.ROUND_RTN)
+    assert (q.rows, q.K) == (0, 128)
+    q = tj.quantize(x0, 1, B.ROUND_SR, seed=1)
+    assert (q.rows, q.K) == (128, 0)
+    r, c = tj.quantize_dual(x0, B.ROUND_SR, seed=1)
+    assert (r.rows, r.K, c.rows, c.K) == (0, 128, 128, 0)
+    # a layer with no tokens: Y and dX are empty, dW is all zeros
+    W = dev_bf16(wl.normal_bf16((64, 128), 0.02, 3))
+    Y, Xq, Wq = tj.linear_fwd(x0, W, B.OUT_F32)
+    assert Y.shape == (0, 64)
+    dY = torch.empty((0, 64), dtype=torch.bfloat16, device=dev)
+    dX, dW = tj.linear_bwd(dY, Xq, Wq, 5, 0, B.OUT_F32)
+    torch.cuda.synchronize()
+    assert dX.shape == (0, 128) and dW.shape == (64, 128)
+    assert torch.count_nonzero(dW).item() == 0
