@@ -392,3 +392,19 @@ def test_empty_inputs_are_accepted_and_write_nothing():
     torch.cuda.synchronize()
     assert dX.shape == (0, 128) and dW.shape == (64, 128)
     assert torch.count_nonzero(dW).item() == 0
+
+
+def test_gemm_longest_reduction():
+    """K = 2^22, the longest reduction the product accepts (its tile offsets are 32-bit): 16 x 16 outputs, split along K."""
+    M = N = 16
+    K = 1 << 22
+    A = oracle.quantize_bf16(wl.normal_bf16((M, K), 1.0, 901), 0, 0)
+    Bq = oracle.quantize_bf16(wl.normal_bf16((N, K), 0.02, 902), 0, 1, seed=3)
+    assert tj.binding.gemm_plan(M, N, K)[2] > 1
+    ref, absref = oracle.gemm_nt(A, Bq)
+    got = tj.gemm_nt(to_dev(A), to_dev(Bq), 1)
+    torch.cuda.synchronize()
+    check_product(got, ref, absref, "gemm 16x16x2^22")
+    with pytest.raises(tj.NVFP4Error):                       # one step beyond is refused on the host
+        bad = tj.alloc_nvfp4(16, 2 * K)
+        tj.gemm_nt(bad, bad, 1)
