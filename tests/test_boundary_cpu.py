@@ -176,3 +176,17 @@ def test_planner_and_workspace_accept_empty_products(lib):
         assert lib.nvfp4_workspace_bytes(B.OP_GEMM, M, K, N, 0) == 0
     for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD_DX, B.OP_LINEAR_BWD_DW, B.OP_LINEAR_BWD):
         assert lib.nvfp4_workspace_bytes(op, 0, 128, 64, 0) > 0
+
+
+def test_gemm_variant_table_reaches_every_kernel_instantiation():
+    """Five workgroup tiles x {single, paired} scale fetch x {one pass, K split}; the 128 x 192 tile exists for the paired
+    fetch only: 18 variants, and the planner picks each for its shape in the table the GPU parity test runs over."""
+    from gemm_variants import VARIANT_SHAPES
+    tiles = [(128, 128), (128, 256), (256, 128), (256, 256)]
+    want = {(bm, bn, ps, sp) for bm, bn in tiles for ps in (False, True) for sp in (False, True)}
+    want |= {(128, 192, True, False), (128, 192, True, True)}
+    assert set(VARIANT_SHAPES) == want
+    for (bm, bn, ps, sp), (M, N, K) in VARIANT_SHAPES.items():
+        pm, pn, split = B.gemm_plan(M, N, K)
+        assert (pm, pn, K % 256 == 0, split > 1) == (bm, bn, ps, sp), (M, N, K)
+        assert M % 64 and N % 4

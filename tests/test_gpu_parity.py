@@ -199,6 +199,26 @@ def test_requant_col(shape, rounding):
     assert_same(got, ref, "requant %s r%d" % (shape, rounding))
 
 
+@pytest.mark.parametrize("rounding,scale_round", [(0, 2), (1, 1)])
+def test_non_default_scale_rounding_in_every_quantizer(rounding, scale_round):
+    """Nearest rounding with the scale rounded up, stochastic rounding with the scale rounded to nearest: the kernel
+    instantiations the defaults never pick, for the column-wise, dual, re-quantizing and 1 x 128 row-wise quantizers."""
+    kw = dict(scale_round=scale_round, seed=12)
+    bits = wl.normal_bf16((272, 208), 1e-3, 41, 1e-2, 30.0)
+    x = dev_bf16(bits)
+    assert_same(tj.quantize(x, 1, rounding, tensor_id=5, **kw), oracle.quantize_bf16(bits, 1, rounding, tensor_id=5, **kw), "col")
+    row, col = tj.quantize_dual(x, rounding, scale_round=scale_round, seed=12, tensor_id_row=3, tensor_id_col=5)
+    assert_same(row, oracle.quantize_bf16(bits, 0, rounding, tensor_id=3, **kw), "dual row")
+    assert_same(col, oracle.quantize_bf16(bits, 1, rounding, tensor_id=5, **kw), "dual col")
+    src = oracle.quantize_bf16(bits, 0, 0)
+    assert_same(tj.quantize(to_dev(src), 1, rounding, tensor_id=6, **kw), oracle.requantize(src, 1, rounding, tensor_id=6, **kw),
+                "requant")
+    wide = wl.student_t_bf16((37, 384), 3.0, 0.1, 42)
+    assert_same(tj.quantize(dev_bf16(wide), 0, rounding, outer=tj.binding.OUTER_BLOCK128, tensor_id=1, **kw),
+                oracle.quantize_bf16(wide, 0, rounding, outer=oracle.OUTER_BLOCK128, tensor_id=1, **kw), "row128",
+                check_amax=(rounding == 0))
+
+
 def test_requant_on_the_truncation_boundary():
     """Q6 of a 256 x 256 tensor with seed 1322: one argument below 1 sits exactly where dropping and rounding its bits
     under 2^-23 give different codes (tests/test_oracle_pins.py shows that on the CPU); the GPU must drop them too."""
@@ -240,6 +260,36 @@ def test_gemm_ragged_large_tiles_sampled_rows(M, N, K, out_dtype):
     rng = np.random.default_rng(M + N)
     rows = np.unique(np.concatenate([[0, M - 1, (M // 128) * 128 - 1, (M // 128) * 128 % M],
                                      rng.choice(M, 40, replace=False)]))
+    ref, absref = oracle.gemm_nt(A, B, rows_a=rows)
+    check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm %dx%dx%d" % (M, N, K))
+
+
+def _variant_cases():
+    from gemm_variants import VARIANT_SHAPES
+    cases, nsplit = [], 0
+    for key, shape in sorted(VARIANT_SHAPES.items()):
+        # one pass: the kernel converts and stores itself, so both output types are kernels of their own;
+        # K split: the kernel writes FP32 partials either way, the output type alternates over the table
+        nsplit += key[3]
+        for out_dtype in ((nsplit & 1,) if key[3] else (0, 1)):
+            cases.append(pytest.param(key, shape, out_dtype, id="%dx%d-ps%d-split%d-out%d" % (*map(int, key), out_dtype)))
+    return cases
+
+
+@pytest.mark.parametrize("key,shape,out_dtype", _variant_cases())
+def test_gemm_every_kernel_instantiation(key, shape, out_dtype):
+    """Every workgroup tile x scale fetch x split x output variant of the product kernel, on a ragged shape for which
+    the planner picks it (checked without a GPU in test_boundary_cpu.py): sampled rows, all columns."""
+    M, N, K = shape
+    pm, pn, split = tj.binding.gemm_plan(M, N, K)
+    assert (pm, pn, K % 256 == 0, split > 1) == key
+    A = oracle.quantize_bf16(wl.normal_bf16((M, K), 1.0, 900 + N, 1e-2, 50.0), 0, 0)
+    B = oracle.quantize_bf16(wl.normal_bf16((N, K), 0.02, 901 + M), 0, 1, seed=6)
+    got = tj.gemm_nt(to_dev(A), to_dev(B), out_dtype)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(M * 31 + N)
+    edge = [0, M - 1, (M // pm) * pm - 1, (M // pm) * pm % M, min(M - 1, pm - 1), min(M - 1, pm)]
+    rows = np.unique(np.concatenate([[r for r in edge if 0 <= r < M], rng.choice(M, min(M, 24), replace=False)]))
     ref, absref = oracle.gemm_nt(A, B, rows_a=rows)
     check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm %dx%dx%d" % (M, N, K))
 
