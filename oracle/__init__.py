@@ -65,6 +65,8 @@ def lib():
         L.oracle_quantize_rows.argtypes = [p, i64, i64, i32, i32, i32, u64, u32, p, p, p, p]
         L.oracle_quantize_rows_y.restype = i32
         L.oracle_quantize_rows_y.argtypes = [p, i64, i64, i32, i32, i32, u64, u32, p, p, p, p, p]
+        L.oracle_quantize_rows_slice.restype = i32
+        L.oracle_quantize_rows_slice.argtypes = [p, i64, i64, i32, i32, i32, u64, u32, i64, f32, p, p, p]
         L.oracle_rand22_fill.restype = None
         L.oracle_rand22_fill.argtypes = [u64, i64, p]
         L.oracle_dequant_f32.restype = i32
@@ -129,6 +131,22 @@ def quantize_f32(x: np.ndarray, rounding: int, scale_round: int = SCALE_DEFAULT,
     if rc != 0:
         raise ValueError("oracle_quantize_rows: bad shape or enum")
     return NVFP4(codes, scales, gscale, float(amax_deq.value), rows, K, outer)
+
+
+def quantize_f32_slice(x: np.ndarray, row0: int, tensor_amax: float, rounding: int, scale_round: int = SCALE_DEFAULT,
+                       seed: int = 0, tensor_id: int = 0) -> NVFP4:
+    """Rows row0 .. row0 + len(x) - 1 of a larger [*, K] tensor with max |.| = tensor_amax (per-tensor outer scale):
+    the bytes those rows have in the whole tensor's quantization (sampled checks on tensors too large to do whole)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, K = x.shape
+    codes = np.zeros((rows, K // 2), dtype=np.uint8)
+    scales = np.zeros((rows, K // 16), dtype=np.uint8)
+    gscale = np.zeros((1,), dtype=np.float32)
+    rc = lib().oracle_quantize_rows_slice(_ptr(x), rows, K, rounding, scale_round, OUTER_TENSOR, seed, tensor_id,
+                                          row0, tensor_amax, _ptr(codes), _ptr(scales), _ptr(gscale))
+    if rc != 0:
+        raise ValueError("oracle_quantize_rows_slice: bad shape or enum")
+    return NVFP4(codes, scales, gscale, float("nan"), rows, K, OUTER_TENSOR)
 
 
 def quantize_bf16(src_bits: np.ndarray, axis: int, rounding: int, **kw) -> NVFP4:

@@ -212,15 +212,18 @@ float oracle_global_scale(float amax)
 static int quantize_rows_impl(const float *x, int64_t rows, int64_t K,
                               int rounding, int scale_round, int outer_mode,
                               uint64_t seed, uint32_t tensor_id,
-                              uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq, float *y_out)
+                              uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq, float *y_out,
+                              int64_t row0, const float *tensor_amax)
 {
-    if (rows < 0 || K < 0 || K % 16) return -1;
+    /* x holds rows row0 .. row0 + rows - 1 of the tensor (row0 = 0: all of it); tensor_amax, when given, is the
+     * whole tensor's max |x| (needed when x is only a slice) */
+    if (rows < 0 || K < 0 || K % 16 || row0 < 0) return -1;
     if (outer_mode == OUTER_BLOCK128 && K % 128) return -1;
     if (outer_mode != OUTER_TENSOR && outer_mode != OUTER_BLOCK128) return -1;
     if (rounding != ROUND_RTN && rounding != ROUND_SR) return -1;
     if (scale_round == SCALE_DEFAULT) scale_round = rounding == ROUND_RTN ? SCALE_NE : SCALE_UP;
     if (scale_round != SCALE_NE && scale_round != SCALE_UP) return -1;
-    if ((double)rows * (double)K > 17179869184.0) return -1;       /* quad index must fit 32 bits */
+    if ((double)(row0 + rows) * (double)K > 17179869184.0) return -1;       /* quad index must fit 32 bits */
 
     const uint64_t key = oracle_stream_key(seed, tensor_id);
     const int64_t outer_len = outer_mode == OUTER_TENSOR ? K : 128;
@@ -230,6 +233,7 @@ static int quantize_rows_impl(const float *x, int64_t rows, int64_t K,
     if (outer_mode == OUTER_TENSOR) {
         float amax = 0.0f;
         for (int64_t r = 0; r < rows; ++r) { float m = abs_max(x + r * K, K); if (m > amax) amax = m; }
+        if (tensor_amax) amax = *tensor_amax;
         tensor_sg = oracle_global_scale(amax);
         gscale[0] = tensor_sg;
     }
@@ -263,7 +267,7 @@ static int quantize_rows_impl(const float *x, int64_t rows, int64_t K,
                     float a = fabsf(y); if (a > 6.0f) a = 6.0f;
                     int m;
                     if (rounding == ROUND_RTN) m = oracle_round_rtn(a);
-                    else m = oracle_round_sr(a, oracle_rand22((uint64_t)(r * K + k), key));
+                    else m = oracle_round_sr(a, oracle_rand22((uint64_t)((row0 + r) * K + k), key));
                     int neg = signbit(xb[i]) != 0;
                     uint8_t nib = (uint8_t)((neg << 3) | m);
                     uint8_t *byte = codes + r * (K / 2) + k / 2;
@@ -286,7 +290,7 @@ int oracle_quantize_rows(const float *x, int64_t rows, int64_t K,
                          uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq)
 {
     return quantize_rows_impl(x, rows, K, rounding, scale_round, outer_mode, seed, tensor_id, codes, scales, gscale,
-                              amax_deq, NULL);
+                              amax_deq, NULL, 0, NULL);
 }
 
 /* test helper: the same, and also the argument y of round_FP4 for every element ([rows][K]) */
@@ -296,7 +300,18 @@ int oracle_quantize_rows_y(const float *x, int64_t rows, int64_t K,
                            uint8_t *codes, uint8_t *scales, float *gscale, float *amax_deq, float *y_out)
 {
     return quantize_rows_impl(x, rows, K, rounding, scale_round, outer_mode, seed, tensor_id, codes, scales, gscale,
-                              amax_deq, y_out);
+                              amax_deq, y_out, 0, NULL);
+}
+
+/* test helper: rows row0 .. row0 + rows - 1 of a larger tensor whose max |x| is tensor_amax (per-tensor outer scale);
+ * the outputs cover the slice only.  The bytes equal those rows of the whole tensor's quantization. */
+int oracle_quantize_rows_slice(const float *x, int64_t rows, int64_t K,
+                               int rounding, int scale_round, int outer_mode,
+                               uint64_t seed, uint32_t tensor_id, int64_t row0, float tensor_amax,
+                               uint8_t *codes, uint8_t *scales, float *gscale)
+{
+    return quantize_rows_impl(x, rows, K, rounding, scale_round, outer_mode, seed, tensor_id, codes, scales, gscale,
+                              NULL, NULL, row0, &tensor_amax);
 }
 
 /* test helper: the 22 random bits of elements 0 .. n-1 of a stream */

@@ -458,3 +458,80 @@ def test_gemm_longest_reduction():
     with pytest.raises(tj.NVFP4Error):                       # one step beyond is refused on the host
         bad = tj.alloc_nvfp4(16, 2 * K)
         tj.gemm_nt(bad, bad, 1)
+
+
+# ------------------------------------------------- more than 2^32 elements (64-bit indexing, sampled)
+
+def _rows_match(q_gpu, row, ref: oracle.NVFP4, what):
+    assert np.array_equal(q_gpu.codes[row].cpu().numpy(), ref.codes[0]), "%s: codes of row %d" % (what, row)
+    assert np.array_equal(q_gpu.scales[row].cpu().numpy(), ref.scales[0]), "%s: scales of row %d" % (what, row)
+    assert np.float32(q_gpu.gscale.cpu().numpy()[0]) == ref.gscale[0], what
+
+
+def test_quantizers_beyond_2_to_32_elements():
+    """A 32800 x 131200 tensor (4.3e9 elements): every quantizer's rows / columns on both sides of element 2^32, the
+    first and the last, against the oracle's slice entry.  The tensor is drawn on the GPU (standard normal, one planted
+    maximum of 40 in the last element) and the sampled rows and columns are copied to the host for the oracle."""
+    B = tj.binding
+    R, C = 32800, 131200
+    assert R * C > 2 ** 32
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20)
+    x = torch.empty((R, C), dtype=torch.bfloat16, device="cuda").normal_(generator=gen)
+    x[R - 1, C - 1] = 40.0
+    ws = tj.alloc_workspace(tj.workspace_bytes(B.OP_QUANTIZE, R, C, 0))
+    amax = float(tj.amax_bf16(x, ws).cpu()[0])
+    assert amax == 40.0
+    rows = [0, 1, R // 2, 2 ** 32 // C, 2 ** 32 // C + 1, R - 1]
+    cols = [0, 1, C // 2, 2 ** 32 // R, 2 ** 32 // R + 1, C - 1]
+    x_rows = {r: x[r].float().cpu().numpy()[None, :] for r in rows}
+    x_cols = {c: x[:, c].float().cpu().numpy()[None, :] for c in cols}
+
+    print("[2^32] row-wise", flush=True)
+    q_rtn = tj.quantize(x, 0, B.ROUND_RTN, ws=ws)
+    for r in rows:
+        _rows_match(q_rtn, r, oracle.quantize_f32_slice(x_rows[r], r, amax, oracle.RTN), "row RTN")
+    last = oracle.quantize_f32_slice(x_rows[R - 1], R - 1, amax, oracle.RTN)
+    amax_deq = float(np.abs(oracle.dequant_f32(last)).max())
+    assert float(q_rtn.amax_deq.cpu()[0]) == amax_deq          # the planted maximum dominates every other value
+    q = tj.quantize(x, 0, B.ROUND_SR, seed=21, tensor_id=3, ws=ws)
+    for r in rows:
+        _rows_match(q, r, oracle.quantize_f32_slice(x_rows[r], r, amax, oracle.SR, seed=21, tensor_id=3), "row SR")
+    del q
+
+    print("[2^32] column-wise", flush=True)
+    q = tj.quantize(x, 1, B.ROUND_SR, seed=21, tensor_id=5, ws=ws)
+    for c in cols:
+        _rows_match(q, c, oracle.quantize_f32_slice(x_cols[c], c, amax, oracle.SR, seed=21, tensor_id=5), "col SR")
+    del q
+
+    print("[2^32] row-wise and column-wise from one read", flush=True)
+    qr, qc = tj.quantize_dual(x, B.ROUND_SR, seed=21, tensor_id_row=3, tensor_id_col=5, ws=ws)
+    for r in rows:
+        _rows_match(qr, r, oracle.quantize_f32_slice(x_rows[r], r, amax, oracle.SR, seed=21, tensor_id=3), "dual row SR")
+    for c in cols:
+        _rows_match(qc, c, oracle.quantize_f32_slice(x_cols[c], c, amax, oracle.SR, seed=21, tensor_id=5), "dual col SR")
+    del qr, qc, x
+
+    print("[2^32] column-wise from the packed tensor", flush=True)
+    q = tj.quantize(q_rtn, 1, B.ROUND_SR, seed=21, tensor_id=6, ws=ws)
+    for c in cols:
+        g = c // 16
+        grp = oracle.NVFP4(q_rtn.codes[:, 8 * g:8 * g + 8].cpu().numpy().copy(), q_rtn.scales[:, g:g + 1].cpu().numpy().copy(),
+                           q_rtn.gscale.cpu().numpy(), amax_deq, R, 16, oracle.OUTER_TENSOR)
+        col = np.ascontiguousarray(oracle.dequant_f32(grp)[:, c % 16])[None, :]
+        _rows_match(q, c, oracle.quantize_f32_slice(col, c, amax_deq, oracle.SR, seed=21, tensor_id=6), "requant SR")
+
+
+@pytest.mark.parametrize("out_dtype", [0, 1])
+def test_gemm_beyond_2_to_32_outputs(out_dtype):
+    """65600 x 65600 outputs (4.3e9) of a K = 64 product: rows on both sides of output 2^31 and 2^32, first and last."""
+    M = N = 65600
+    K = 64
+    A = oracle.quantize_bf16(wl.normal_bf16((M, K), 1.0, 31, 1e-2, 50.0), 0, 0)
+    Bq = oracle.quantize_bf16(wl.normal_bf16((N, K), 0.02, 32), 0, 1, seed=4)
+    got = tj.gemm_nt(to_dev(A), to_dev(Bq), out_dtype)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 2 ** 31 // N, 2 ** 31 // N + 1, 2 ** 32 // N, 2 ** 32 // N + 1, M - 2, M - 1])
+    ref, absref = oracle.gemm_nt(A, Bq, rows_a=rows)
+    check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm %dx%dx%d" % (M, N, K))

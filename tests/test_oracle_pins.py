@@ -508,3 +508,21 @@ def test_sr_boundary_case_is_on_the_truncation_boundary():
     # the same call through the ordinary entry point gives the same bytes
     ref = oracle.requantize(src, 1, oracle.SR, seed=seed, tensor_id=tid)
     assert np.array_equal(ref.codes, codes) and np.array_equal(ref.scales, scales)
+
+
+def test_slice_helper_gives_the_rows_of_the_whole_quantization():
+    """The slice entry (rows from row0 on, the tensor's maximum passed in) is the full quantizer restricted to those rows,
+    for both roundings; it exists for sampled checks of tensors too large to quantize whole on the CPU."""
+    x = oracle.bf16_to_f32(wl.student_t_bf16((96, 160), 3.0, 0.1, 71))
+    amax = float(np.abs(x).max())
+    for rounding in (oracle.RTN, oracle.SR):
+        full = oracle.quantize_f32(x, rounding, seed=5, tensor_id=12)
+        for row0, n in ((0, 96), (17, 1), (40, 23), (95, 1)):
+            part = oracle.quantize_f32_slice(x[row0:row0 + n], row0, amax, rounding, seed=5, tensor_id=12)
+            assert part.gscale[0] == full.gscale[0]
+            assert np.array_equal(part.codes, full.codes[row0:row0 + n])
+            assert np.array_equal(part.scales, full.scales[row0:row0 + n])
+    # a different row offset moves the random stream (stochastic rounding only)
+    a = oracle.quantize_f32_slice(x[:8], 0, amax, oracle.SR, seed=5, tensor_id=12)
+    b = oracle.quantize_f32_slice(x[:8], 8, amax, oracle.SR, seed=5, tensor_id=12)
+    assert not np.array_equal(a.codes, b.codes) and np.array_equal(a.scales, b.scales)
