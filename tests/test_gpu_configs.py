@@ -106,7 +106,7 @@ def _cases(cfg):
     return [pytest.param(cfg, li, id="%s-%s" % (cfg, lin[0])) for li, lin in enumerate(wl.config_linears(cfg))]
 
 
-@pytest.mark.parametrize("cfg,li", _cases("cfg2_block768") + _cases("cfg3_block1024") + _cases("cfg5_square8192"))
+@pytest.mark.parametrize("cfg,li", _cases("cfg1_single") + _cases("cfg2_block768") + _cases("cfg3_block1024") + _cases("cfg5_square8192"))
 def test_full_size_linear(cfg, li):
     name, N, D, C, seed, kind = wl.config_linears(cfg)[li]
     run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed=0)
