@@ -31,15 +31,16 @@
  *       rounding, UP for stochastic rounding (a scale rounded down would clip
  *       the block maximum and bias the estimate).
  *   R4  Deterministic rounding breaks ties toward the even code.
- *   R5  Stochastic rounding: the paper's xi ~ U(-D/2, D/2) with D = q2 - q1 and
- *       "x + xi <= midpoint -> q1" is taken on a discrete uniform of 22 bits:
- *       with f = (a - q1)/D and L = floor(f * 2^22), a is rounded up iff
- *       u + L >= 2^22 for u uniform on {0..2^22-1}; so P(q2) = L / 2^22.  Below
- *       1 (the E2M1 subnormal range) a is first truncated to a multiple of 2^-23
- *       (it loses less than 2^-23, 5e-7 of the grid step), which makes f * 2^22 an
- *       integer there; from 1 to 6 a binary32 value has
- *       at most 22 bits below the E2M1 mantissa bit, so L = f * 2^22 exactly and
- *       the rounding is exactly unbiased on that image of a.
+ *   R5  Stochastic rounding: the paper's rule is "x + xi <= midpoint -> q1" with
+ *       xi ~ U(-D/2, D/2), D = q2 - q1.  With f = (a - q1)/D and v = xi/D + 1/2
+ *       (uniform on the unit interval) that is "q2 iff f + v > 1".  The one change
+ *       made here is the random variate: v is drawn from the 22-bit grid
+ *       {0, 1, .., 2^22-1} / 2^22, and a goes to q2 iff f + u/2^22 >= 1, i.e. iff
+ *       u + floor(f * 2^22) >= 2^22.  So P(q2) = floor(f * 2^22) / 2^22.  From 1 to
+ *       6 a binary32 value has at most 22 bits below the E2M1 mantissa bit, f * 2^22
+ *       is an integer and the rounding is exactly unbiased; below 1 (the E2M1
+ *       subnormal range) the bits of a below 2^-23 cannot reach the decision, and
+ *       the mean falls short of a by less than 2^-23 (toward zero).
  *   R6  The 22 random bits of output element e (index in the quantized
  *       operand's own [rows x K] view) come from a counter-based 32-bit hash h of
  *       the quad index e>>2, keyed by (seed, tensor id): element i = e&3 of the
@@ -157,14 +158,13 @@ int oracle_round_rtn(float a)
 /* Sec. 2.1 round_{FP4,S} with the discrete uniform of R5; u22 in [0, 2^22) */
 int oracle_round_sr(float a, uint32_t u22)
 {
-    if (a < 1.0f) a = floorf(a * 8388608.0f) * (1.0f / 8388608.0f);  /* R5: 2^-23 grid below 1, toward zero */
     if (a >= 6.0f) return 7;
     int i1 = 0;
     for (int i = 0; i < 7; ++i)
         if (FP4_VALUES[i] <= a) i1 = i;                               /* q1 <= a < q2 */
     float q1 = FP4_VALUES[i1], q2 = FP4_VALUES[i1 + 1];
     double f = ((double)a - (double)q1) / ((double)q2 - (double)q1);
-    uint32_t L = (uint32_t)floor(f * 4194304.0);
+    uint32_t L = (uint32_t)floor(f * 4194304.0);                      /* R5: q2 iff f + u / 2^22 >= 1 */
     return (u22 + L >= 4194304u) ? i1 + 1 : i1;
 }
 
