@@ -52,7 +52,9 @@ extern "C" {
 enum {
     NVFP4_OK = 0,
     NVFP4_ERR_NULL = -1,      /* a required pointer is NULL */
-    NVFP4_ERR_SHAPE = -2,     /* negative size, K % 16 != 0, K % 128 != 0 in BLOCK128 mode, > 2^33 elements */
+    NVFP4_ERR_SHAPE = -2,     /* negative size; grouped axis K % 16 != 0 (K % 128 != 0 in BLOCK128 mode); more than 2^33
+                                 elements; C % 8 != 0 for a column-wise bf16 source; for the products: reduction
+                                 length not a multiple of 64 or above 2^22 */
     NVFP4_ERR_ENUM = -3,      /* unknown enum value, or a combination this build does not provide */
     NVFP4_ERR_WORKSPACE = -4, /* ws is NULL or smaller than nvfp4_workspace_bytes() */
     NVFP4_ERR_ALIGN = -5,     /* a device pointer is not 16-byte aligned */
@@ -117,6 +119,9 @@ int nvfp4_quantize_dual(const void *src, int64_t R, int64_t C, const nvfp4_qcfg 
  * Out[M x N] = A[M x K] * B[N x K]^T on two quantized operands grouped along K (Sec. 2.3: all three products take
  * this form).  Products of dequantized 16-bit values are exact; accumulation is FP32; the outer scales multiply
  * the accumulator at the end; Out is row-major bf16 or f32.  Both operands must be in TENSOR outer mode.
+ * Limits: A->K == B->K, K % 64 == 0 and K <= 2^22 (SHAPE otherwise); any M = A->rows, N = B->rows.  ws: at least
+ * nvfp4_workspace_bytes(NVFP4_OP_GEMM, M, K, N, 0) bytes (0 for most shapes; FP32 partial sums when the planner
+ * splits the reduction).  Errors: NULL, SHAPE, ENUM, WORKSPACE, ALIGN, MISMATCH.
  */
 int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype,
                   void *ws, size_t ws_bytes, void *stream);
@@ -124,6 +129,7 @@ int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int o
 /*
  * Forward (Sec. 2.3, first line): quantizes X [N x D] and W [C x D] (bf16, round-to-nearest, groups along D) into
  * Xq_ctx / Wq_ctx, which the caller keeps for the backward calls, and writes Y [N x C].
+ * Limits: D % 64 == 0 and D <= 2^22 (D is the reduction length); any N, C.  X, W, Y 16-byte aligned.
  */
 int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t C,
                      void *Y, int out_dtype, nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx,
@@ -140,6 +146,8 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
 /*
  * Weight gradient (Sec. 2.3, third line): dW [C x D] = Q5_S(dY^T) x Q6_S(X_hat); both operands re-grouped along N
  * with stochastic rounding.  Streams: tensor ids layer_id*8+5 and +6.
+ * Limits: N % 64 == 0 and N <= 2^22 (reduction length); C % 8 == 0 (128-bit loads along the rows of dY);
+ * D % 16 == 0.
  */
 int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C,
                         void *dW, int out_dtype, uint64_t seed, uint32_t layer_id,
@@ -149,7 +157,7 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
  * Both gradients of one layer in one call (Sec. 2.3, second and third line).  Same results, byte for byte, as
  * nvfp4_linear_bwd_dx followed by nvfp4_linear_bwd_dw with the same seed and layer_id, but dY is read once for its
  * maximum and once more for both of its quantizations (Q3 row-wise and Q5 column-wise leave one kernel).
- * Needs C % 64 == 0 and N % 64 == 0.
+ * Limits: C % 64 == 0, N % 64 == 0, both <= 2^22 (each is the reduction length of one product); D % 16 == 0.
  */
 int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx,
                      int64_t N, int64_t D, int64_t C, void *dX, void *dW, int out_dtype,
@@ -165,7 +173,8 @@ size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_
  * output) and the number of K splits (> 1 means FP32 partials in ws plus a reduction kernel).  Host-only helper. */
 int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, int *tile_m, int *tile_n, int *split);
 
-/* Tensor maximum of |x| of a bf16 device array of n elements (n % 8 == 0) into amax_out (device [1]). */
+/* Tensor maximum of |x| of a bf16 device array of n elements (n % 8 == 0) into amax_out (device [1]): the max |X| of
+ * Sec. 2.2's S_global = max |X| / (448 * 6) for a per-tensor outer group.  ws: nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE, ..). */
 int nvfp4_amax_bf16(const void *src, int64_t n, float *amax_out, void *ws, size_t ws_bytes, void *stream);
 
 /* The 64-bit stream key the stochastic-rounding generator derives from (seed, tensor_id); host-only helper. */

@@ -214,6 +214,15 @@ def quantize_dual(src: torch.Tensor, rounding: int, out_row: Optional[NVFP4Tenso
     return out_row, out_col
 
 
+def _check_bf16(t: torch.Tensor, what: str):
+    assert t.dtype == torch.bfloat16 and t.dim() == 2 and t.is_contiguous() and t.is_cuda, what + ": bf16, 2-D, contiguous, on the GPU"
+
+
+def _check_out(t: torch.Tensor, shape, out_dtype: int, what: str):
+    want = torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32
+    assert t.dtype == want and tuple(t.shape) == tuple(shape) and t.is_contiguous() and t.is_cuda, what
+
+
 def _out_tensor(M, N, out_dtype, device):
     return torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32, device=device)
 
@@ -234,11 +243,14 @@ def gemm_nt(A: NVFP4Tensor, B: NVFP4Tensor, out_dtype: int = OUT_BF16, out: Opti
 def linear_fwd(X: torch.Tensor, W: torch.Tensor, out_dtype: int = OUT_BF16, *, Y: Optional[torch.Tensor] = None,
                Xq: Optional[NVFP4Tensor] = None, Wq: Optional[NVFP4Tensor] = None,
                ws: Optional[torch.Tensor] = None, outer: int = OUTER_TENSOR):
+    _check_bf16(X, "X")
+    _check_bf16(W, "W")
     N, D = X.shape
     Cc, D2 = W.shape
     assert D == D2
     dev = X.device
     Y = _out_tensor(N, Cc, out_dtype, dev) if Y is None else Y
+    _check_out(Y, (N, Cc), out_dtype, "Y")
     Xq = alloc_nvfp4(N, D, outer, dev) if Xq is None else Xq
     Wq = alloc_nvfp4(Cc, D, outer, dev) if Wq is None else Wq
     ws = alloc_workspace(workspace_bytes(OP_LINEAR_FWD, N, D, Cc, outer), dev) if ws is None else ws
@@ -253,10 +265,12 @@ def linear_fwd(X: torch.Tensor, W: torch.Tensor, out_dtype: int = OUT_BF16, *, Y
 
 def linear_bwd_dx(dY: torch.Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
                   dX: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _check_bf16(dY, "dY")
     N, Cc = dY.shape
     D = Wq.K
     dev = dY.device
     dX = _out_tensor(N, D, out_dtype, dev) if dX is None else dX
+    _check_out(dX, (N, D), out_dtype, "dX")
     ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DX, N, D, Cc), dev) if ws is None else ws
     cw = Wq.c_struct()
     rc = lib().nvfp4_linear_bwd_dx(_ptr(dY), C.byref(cw), N, D, Cc, _ptr(dX), out_dtype, seed, layer_id,
@@ -267,10 +281,12 @@ def linear_bwd_dx(dY: torch.Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, o
 
 def linear_bwd_dw(dY: torch.Tensor, Xq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
                   dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _check_bf16(dY, "dY")
     N, Cc = dY.shape
     D = Xq.K
     dev = dY.device
     dW = _out_tensor(Cc, D, out_dtype, dev) if dW is None else dW
+    _check_out(dW, (Cc, D), out_dtype, "dW")
     ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DW, N, D, Cc), dev) if ws is None else ws
     cx = Xq.c_struct()
     rc = lib().nvfp4_linear_bwd_dw(_ptr(dY), C.byref(cx), N, D, Cc, _ptr(dW), out_dtype, seed, layer_id,
@@ -282,11 +298,14 @@ def linear_bwd_dw(dY: torch.Tensor, Xq: NVFP4Tensor, seed: int, layer_id: int, o
 def linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
                dX: Optional[torch.Tensor] = None, dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
     """nvfp4_linear_bwd: both gradients, dY read once for its maximum and once for both quantizations."""
+    _check_bf16(dY, "dY")
     N, Cc = dY.shape
     D = Xq.K
     dev = dY.device
     dX = _out_tensor(N, D, out_dtype, dev) if dX is None else dX
     dW = _out_tensor(Cc, D, out_dtype, dev) if dW is None else dW
+    _check_out(dX, (N, D), out_dtype, "dX")
+    _check_out(dW, (Cc, D), out_dtype, "dW")
     ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD, N, D, Cc), dev) if ws is None else ws
     cx, cw = Xq.c_struct(), Wq.c_struct()
     rc = lib().nvfp4_linear_bwd(_ptr(dY), C.byref(cx), C.byref(cw), N, D, Cc, _ptr(dX), _ptr(dW), out_dtype, seed,

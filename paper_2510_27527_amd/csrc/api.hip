@@ -66,6 +66,11 @@ int check_tensor_ptrs(const nvfp4_tensor *t)
     return NVFP4_OK;
 }
 
+// reduction length of a product: whole 64-wide chunks, and short enough for the kernel's 32-bit per-lane offsets
+// (row-in-tile * K / 2 + piece offset, row-in-tile <= 255)
+constexpr int64_t kMaxReduction = (int64_t)1 << 22;
+int check_reduction(int64_t K) { return (K % 64 != 0 || K > kMaxReduction) ? NVFP4_ERR_SHAPE : NVFP4_OK; }
+
 // a gemm operand must be a finished TENSOR-mode operand with K % 64 == 0
 int check_gemm_operand(const nvfp4_tensor *t)
 {
@@ -74,8 +79,7 @@ int check_gemm_operand(const nvfp4_tensor *t)
     if (t->outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;
     rc = check_shape(t->rows, t->K, t->outer_mode);
     if (rc) return rc;
-    if (t->K % 64 != 0 || t->K > ((int64_t)1 << 22)) return NVFP4_ERR_SHAPE;   // 32-bit tile offsets in the kernel
-    return NVFP4_OK;
+    return check_reduction(t->K);
 }
 
 struct QuantPlan {
@@ -410,7 +414,7 @@ int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t
     if (!X || !W) return NVFP4_ERR_NULL;
     if (outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;      // the products take tensor-mode operands
     if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
-    if (D % 64 != 0) return NVFP4_ERR_SHAPE;
+    if (check_reduction(D)) return NVFP4_ERR_SHAPE;
     int rc = check_out(Y, out_dtype);
     if (rc) return rc;
     nvfp4_qcfg cfg{};
@@ -440,7 +444,7 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
 {
     if (!dY || !Wq_ctx) return NVFP4_ERR_NULL;
     if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
-    if (C % 64 != 0) return NVFP4_ERR_SHAPE;
+    if (check_reduction(C)) return NVFP4_ERR_SHAPE;
     int rc = check_out(dX, out_dtype);
     if (rc) return rc;
     if (Wq_ctx->rows != C || Wq_ctx->K != D) return NVFP4_ERR_MISMATCH;
@@ -479,7 +483,7 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
 {
     if (!dY || !Xq_ctx) return NVFP4_ERR_NULL;
     if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
-    if (N % 64 != 0) return NVFP4_ERR_SHAPE;
+    if (check_reduction(N)) return NVFP4_ERR_SHAPE;
     int rc = check_out(dW, out_dtype);
     if (rc) return rc;
     if (Xq_ctx->rows != N || Xq_ctx->K != D) return NVFP4_ERR_MISMATCH;
@@ -519,7 +523,7 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
 {
     if (!dY || !Xq_ctx || !Wq_ctx) return NVFP4_ERR_NULL;
     if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
-    if (C % 64 != 0 || N % 64 != 0) return NVFP4_ERR_SHAPE;
+    if (check_reduction(C) || check_reduction(N)) return NVFP4_ERR_SHAPE;
     int rc = check_out(dX, out_dtype);
     if (rc) return rc;
     rc = check_out(dW, out_dtype);

@@ -1,10 +1,5 @@
 // Host side of the NT GEMM on two packed NVFP4 operands (tile / split planner, launcher) and the split-K reduction.
 // The product kernel itself lives in gemm_kernel.h and is instantiated slice by slice in gemm_inst.hip.
-#ifdef TJ_DEV_FORCE
-#include <stdio.h>
-#include <stdlib.h>
-#endif
-
 #include "gemm_args.h"
 #include "internal.h"
 
@@ -82,22 +77,12 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
     Plan best{3, 1, (int)chunks};
     if (M <= 0 || N <= 0 || chunks == 0) return best;      // nothing to tile (empty output or empty reduction)
     double best_t = 1e300;
-#ifdef TJ_DEV_FORCE
-    int force_tile = -1, force_split = 0;
-    if (const char *f = getenv("TJ_FORCE")) sscanf(f, "%d,%d", &force_tile, &force_split);
-#endif
     for (int t = 0; t < kNumTiles; ++t) {
         if (t == 4 && K % 256 != 0) continue;
-#ifdef TJ_DEV_FORCE
-        if (force_tile >= 0 && t != force_tile) continue;
-#endif
         const int64_t bm = 64 * kTiles[t].tm, bn = 64 * kTiles[t].tn;
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         for (int split = 1; split <= 16; ++split) {
             if (split > 1 && chunks / split < 8) break;
-#ifdef TJ_DEV_FORCE
-            if (force_split > 0 && split != force_split) continue;
-#endif
             int64_t cps = (chunks + split - 1) / split;
             if (chunks % 4 == 0) cps = (cps + 3) / 4 * 4;                       // splits on 256-k boundaries
             if (split > 1 && (chunks + cps - 1) / cps != split) continue;      // same launch as a smaller split

@@ -415,13 +415,10 @@ hipError_t launch_cfg(const GemmArgs &g, dim3 grid, hipStream_t st)
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int lds = 3 * ((BM + BN) * 2 * kNC * 16 + (BM + BN) * (PS ? 16 : kNC * 4));
     auto kern = gemm_nt_kernel<TM, TN, kNC, OUT, PS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per instantiation; the initialisation of a function-local static is thread-safe
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, g);
     return hipGetLastError();
 }

@@ -6,7 +6,8 @@ caller-supplied workspace.  Checked against the CPU oracle:
   * the backward operands Q3..Q6 (nvfp4_quantize with the layer's stream ids): every byte;
   * the fused backward's dX, dW are the bytes of the separate nvfp4_linear_bwd_dx / _dw calls;
   * Y, dX, dW on sampled rows (all columns), within 2^-8 |ref| + 1e-6 sum_k |a||b| of the oracle's float64 product of
-    the same dequantized operands (bf16 output: its rounding alone is up to 2^-9 relative).
+    the same dequantized operands (bf16 output: its rounding alone is up to 2^-9 relative);
+  * the first linear of every workload once more with FP32 outputs, held to the stated bound 1e-3 |ref| + 1e-6 sum_k |a||b|.
 The quantizer stress tensor is compared in full.
 """
 import sys
@@ -57,7 +58,8 @@ def same_bytes(q_gpu, q_ref: oracle.NVFP4, what, check_amax=False):
 def product_ok(got_rows: torch.Tensor, ref, absref, what):
     g = got_rows.double().cpu().numpy()
     err = np.abs(g - ref)
-    tol = 2.0 ** -8 * np.abs(ref) + 1e-6 * absref + 1e-30
+    rel = 1e-3 if got_rows.dtype == torch.float32 else 2.0 ** -8
+    tol = rel * np.abs(ref) + 1e-6 * absref + 1e-30
     worst = np.unravel_index(np.argmax(err - tol), err.shape)
     assert np.all(err <= tol), "%s: err %.3e tol %.3e at %s" % (what, err[worst], tol[worst], worst)
 
@@ -92,14 +94,27 @@ def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed):
     torch.cuda.synchronize()
     assert torch.equal(dX, dX1) and torch.equal(dW, dW1), "fused backward differs from the separate calls"
 
+    outs = {"Y": Y, "dX": dX, "dW": dW}
+    outs32 = {}
+    if li == 0:
+        # the same layer with FP32 outputs: the 1e-3 bound is stated on the value before any bf16 rounding
+        say("[%s %s] FP32-output run" % (cfg, name))
+        del dX1, dW1
+        Y32, _, _ = tj.linear_fwd(X, W, B.OUT_F32, Xq=Xq, Wq=Wq, ws=ws)
+        dX32, dW32 = tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_F32, ws=ws)
+        torch.cuda.synchronize()
+        outs32 = {"Y": Y32, "dX": dX32, "dW": dW32}
     rng = np.random.default_rng(seed)
-    for pname, got, qa, qb in (("Y", Y, oXq, oWq), ("dX", dX, o3, o4), ("dW", dW, o5, o6)):
+    for pname, qa, qb in (("Y", oXq, oWq), ("dX", o3, o4), ("dW", o5, o6)):
         say("[%s %s] oracle product %s on %d sampled rows" % (cfg, name, pname, min(SAMPLE_ROWS, qa.rows)))
         rows = np.sort(rng.choice(qa.rows, min(SAMPLE_ROWS, qa.rows), replace=False))
         rows[0], rows[-1] = 0, qa.rows - 1                        # the corners are always in
         rows = np.unique(rows)
         ref, absref = oracle.gemm_nt(qa, qb, rows_a=rows)
-        product_ok(got[torch.from_numpy(rows).cuda()], ref, absref, "%s %s %s" % (cfg, name, pname))
+        idx = torch.from_numpy(rows).cuda()
+        product_ok(outs[pname][idx], ref, absref, "%s %s %s" % (cfg, name, pname))
+        if pname in outs32:
+            product_ok(outs32[pname][idx], ref, absref, "%s %s %s (FP32 output)" % (cfg, name, pname))
 
 
 def _cases(cfg):

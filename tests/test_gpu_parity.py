@@ -113,8 +113,19 @@ def test_quant_row_amax_supplied_and_edge_values():
     assert_same(got, ref, "amax_in")
     z = np.zeros((4, 64), dtype=np.uint16)
     assert_same(tj.quantize(dev_bf16(z), 0, 1, seed=1), oracle.quantize_bf16(z, 0, 1, seed=1), "zeros")
+    # deterministic rounding also reports the largest dequantized magnitude (what a later re-quantization takes as its
+    # tensor maximum): 0 for an all-zero tensor, and for a floored outer scale (maximum below 2688 * 2^-100) the
+    # reduction over all groups instead of the closed form
+    zq = tj.quantize(dev_bf16(z), 0, 0)
+    zq.amax_deq.fill_(123.0)                       # stale value: the call must overwrite it
+    assert_same(tj.quantize(dev_bf16(z), 0, 0, zq), oracle.quantize_bf16(z, 0, 0), "zeros nearest", check_amax=True)
     tiny = wl.f32_to_bf16(np.full((2, 32), 1e-38, dtype=np.float32))
-    assert_same(tj.quantize(dev_bf16(tiny), 0, 0), oracle.quantize_bf16(tiny, 0, 0), "tiny")
+    assert_same(tj.quantize(dev_bf16(tiny), 0, 0), oracle.quantize_bf16(tiny, 0, 0), "tiny", check_amax=True)
+    rng = np.random.default_rng(301)
+    tiny2 = wl.f32_to_bf16((rng.uniform(0.1, 1.0, (300, 128)) * 1e-28).astype(np.float32))     # several workgroups
+    ref = oracle.quantize_bf16(tiny2, 0, 0)
+    assert ref.gscale[0] == np.float32(2.0 ** -100) and ref.amax_deq > 0
+    assert_same(tj.quantize(dev_bf16(tiny2), 0, 0), ref, "tiny, many groups", check_amax=True)
     huge = wl.f32_to_bf16(np.full((2, 32), 3e38, dtype=np.float32))
     assert_same(tj.quantize(dev_bf16(huge), 0, 0), oracle.quantize_bf16(huge, 0, 0), "huge")
 
