@@ -19,6 +19,8 @@
  *     The library allocates nothing, frees nothing and never synchronises: each
  *     call validates its arguments on the host, then enqueues kernels on
  *     `stream` (a hipStream_t passed as void*, NULL = default stream) and returns.
+ *     Its only state is the per-device address of a static scratch array
+ *     (nvfp4_gemm_nt_static), looked up under a lock.
  *   - Descriptor structs (nvfp4_tensor, nvfp4_qcfg) are HOST memory, read during
  *     the call only.
  *   - Return value: 0 on success, a negative NVFP4_ERR_* otherwise; on error
@@ -59,8 +61,13 @@ enum {
     NVFP4_ERR_WORKSPACE = -4, /* ws is NULL or smaller than nvfp4_workspace_bytes() */
     NVFP4_ERR_ALIGN = -5,     /* a device pointer is not 16-byte aligned */
     NVFP4_ERR_MISMATCH = -6,  /* operand descriptors disagree with each other or with N, D, C */
-    NVFP4_ERR_HIP = -7        /* a HIP launch failed; see hipGetLastError() */
+    NVFP4_ERR_HIP = -7,       /* a HIP launch failed; see hipGetLastError() */
+    NVFP4_ERR_SCRATCH = -8    /* nvfp4_gemm_nt_static: the product needs more than NVFP4_STATIC_SCRATCH_BYTES */
 };
+
+/* Size of the library's static device scratch array (one per GPU, held from the first use of
+ * nvfp4_gemm_nt_static on that GPU until the process ends). */
+#define NVFP4_STATIC_SCRATCH_BYTES (64u << 20)
 
 enum { NVFP4_ROUND_RTN = 0, NVFP4_ROUND_SR = 1 };                 /* Sec. 2.1: deterministic / stochastic   */
 enum { NVFP4_SCALE_DEFAULT = 0, NVFP4_SCALE_NE = 1, NVFP4_SCALE_UP = 2 }; /* E4M3 rounding of S_block; DEFAULT = NE for RTN, UP for SR */
@@ -125,6 +132,18 @@ int nvfp4_quantize_dual(const void *src, int64_t R, int64_t C, const nvfp4_qcfg 
  */
 int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype,
                   void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * nvfp4_gemm_nt for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and the same bytes
+ * in Out as nvfp4_gemm_nt, but the scratch memory a split reduction needs (FP32 partial sums) is a static device array
+ * of NVFP4_STATIC_SCRATCH_BYTES inside the library; the call allocates and frees nothing (the array's address is
+ * looked up once per device on the first call there).  A product whose nvfp4_workspace_bytes(NVFP4_OP_GEMM, ..)
+ * exceeds the array returns NVFP4_ERR_SCRATCH and enqueues nothing.  Every call on one GPU uses that GPU's one array:
+ * calls that overlap in time on a GPU (two streams, two threads) race on it; calls on one stream are safe.  Nothing
+ * in the array has to be zero at entry (every partial sum that is read has been written by the same call).
+ */
+int nvfp4_gemm_nt_static(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *stream);
 
 /*
  * Forward (Sec. 2.3, first line): quantizes X [N x D] and W [C x D] (bf16, round-to-nearest, groups along D) into

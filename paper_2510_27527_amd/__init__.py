@@ -5,5 +5,6 @@ its HIP sources (``csrc/``), the build step (``build.py``) and a thin ctypes bin
 (``binding.py``) with the same call names.
 """
 from . import binding  # noqa: F401
-from .binding import (NVFP4Error, NVFP4Tensor, alloc_nvfp4, alloc_workspace, amax_bf16, gemm_nt, linear_bwd_dw,  # noqa: F401
+from .binding import (NVFP4Error, NVFP4Tensor, alloc_nvfp4, alloc_workspace, amax_bf16, gemm_nt, gemm_nt_static,  # noqa: F401
+                      linear_bwd_dw,
                       linear_bwd, linear_bwd_dx, linear_fwd, quantize, quantize_dual, stream_key, workspace_bytes)

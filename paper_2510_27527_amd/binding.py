@@ -24,7 +24,7 @@ SRC_BF16, SRC_NVFP4 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW, OP_LINEAR_BWD = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd",
+EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_gemm_nt_static", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd",
            "nvfp4_workspace_bytes", "nvfp4_gemm_plan", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
 
 
@@ -62,6 +62,8 @@ def lib():
                                           vp]
         L.nvfp4_gemm_nt.restype = i32
         L.nvfp4_gemm_nt.argtypes = [C.POINTER(CTensor), C.POINTER(CTensor), vp, i32, vp, sz, vp]
+        L.nvfp4_gemm_nt_static.restype = i32
+        L.nvfp4_gemm_nt_static.argtypes = [C.POINTER(CTensor), C.POINTER(CTensor), vp, i32, vp]
         L.nvfp4_linear_fwd.restype = i32
         L.nvfp4_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, i32, C.POINTER(CTensor), C.POINTER(CTensor),
                                        i32, vp, sz, vp]
@@ -237,6 +239,19 @@ def gemm_nt(A: NVFP4Tensor, B: NVFP4Tensor, out_dtype: int = OUT_BF16, out: Opti
     ca, cb = A.c_struct(), B.c_struct()
     rc = lib().nvfp4_gemm_nt(C.byref(ca), C.byref(cb), _ptr(out), out_dtype, _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_gemm_nt")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+ERR_SCRATCH = -8
+
+
+def gemm_nt_static(A: NVFP4Tensor, B: NVFP4Tensor, out: torch.Tensor, out_dtype: int = OUT_BF16) -> torch.Tensor:
+    """nvfp4_gemm_nt_static: the product with the library's static scratch array; `out` is the caller's."""
+    _check_out(out, (A.rows, B.rows), out_dtype, "out")
+    ca, cb = A.c_struct(), B.c_struct()
+    rc = lib().nvfp4_gemm_nt_static(C.byref(ca), C.byref(cb), _ptr(out), out_dtype, _stream())
+    _check(rc, "nvfp4_gemm_nt_static")
     return out
 
 

@@ -2,8 +2,16 @@
 // of the kernels into the four calls of the NVFP4 linear layer (TetraJet-v2 Sec. 2.3).
 // Validation happens before the first HIP call, so every error path can be exercised on a
 // machine without a GPU.
+#include <mutex>
+
 #include "../../include/tjnvfp4.h"
 #include "internal.h"
+
+// Scratch memory of the entry point that allocates nothing (nvfp4_gemm_nt_static): one copy per GPU, at an address
+// of its own on each, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the address that call returns.
+constexpr size_t kStaticScratchBytes = (size_t)NVFP4_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace tj {
 
@@ -268,6 +276,25 @@ int check_out(const void *p, int out_dtype)
     return NVFP4_OK;
 }
 
+// device address of the static scratch array on the current device, looked up once per device
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return NVFP4_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return NVFP4_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return NVFP4_OK;
+}
+
 // carve a temporary operand [rows x K] out of the workspace
 bool carve_tensor(Carver &cv, int64_t rows, int64_t K, nvfp4_tensor *t)
 {
@@ -300,6 +327,7 @@ const char *nvfp4_strerror(int code)
         case NVFP4_ERR_ALIGN: return "device pointer not 16-byte aligned";
         case NVFP4_ERR_MISMATCH: return "operand descriptors disagree";
         case NVFP4_ERR_HIP: return "HIP launch failed";
+        case NVFP4_ERR_SCRATCH: return "the product needs more scratch memory than the library's static array holds";
         default: return "unknown error code";
     }
 }
@@ -405,6 +433,25 @@ int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int o
     if (gemm_workspace_bytes(A->rows, B->rows, A->K) > 0 && (!ws || ws_bytes < gemm_workspace_bytes(A->rows, B->rows, A->K)))
         return NVFP4_ERR_WORKSPACE;
     return run_gemm(A, B, Out, out_dtype, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_gemm_nt_static(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *stream)
+{
+    int rc = check_gemm_operand(A);
+    if (rc) return rc;
+    rc = check_gemm_operand(B);
+    if (rc) return rc;
+    rc = check_out(Out, out_dtype);
+    if (rc) return rc;
+    if (A->K != B->K) return NVFP4_ERR_MISMATCH;
+    const size_t need = gemm_workspace_bytes(A->rows, B->rows, A->K);
+    if (need > kStaticScratchBytes) return NVFP4_ERR_SCRATCH;
+    void *ws = nullptr;
+    if (need > 0) {
+        rc = static_scratch(&ws);
+        if (rc) return rc;
+    }
+    return run_gemm(A, B, Out, out_dtype, ws, need, static_cast<hipStream_t>(stream));
 }
 
 int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t C, void *Y, int out_dtype,

@@ -36,7 +36,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_version_and_strerror(lib):
     assert b"gfx950" in lib.nvfp4_version()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert lib.nvfp4_strerror(code) not in (None, b"unknown error code")
     assert lib.nvfp4_strerror(-99) == b"unknown error code"
 
@@ -190,3 +190,24 @@ def test_gemm_variant_table_reaches_every_kernel_instantiation():
         pm, pn, split = B.gemm_plan(M, N, K)
         assert (pm, pn, K % 256 == 0, split > 1) == (bm, bn, ps, sp), (M, N, K)
         assert M % 64 and N % 4
+
+
+def test_static_scratch_entry_rejects_bad_arguments_and_oversized_products(lib):
+    """nvfp4_gemm_nt_static validates like nvfp4_gemm_nt and, before any HIP call, refuses a product whose split
+    reduction needs more scratch than the library's static array."""
+    ok = _tensor(256, 512)
+    assert lib.nvfp4_gemm_nt_static(None, C.byref(ok), FAKE, 0, None) == -1
+    assert lib.nvfp4_gemm_nt_static(C.byref(ok), C.byref(ok), None, 0, None) == -1
+    assert lib.nvfp4_gemm_nt_static(C.byref(ok), C.byref(ok), FAKE, 5, None) == -3
+    assert lib.nvfp4_gemm_nt_static(C.byref(ok), C.byref(ok), FAKE + 4, 0, None) == -5
+    assert lib.nvfp4_gemm_nt_static(C.byref(ok), C.byref(_tensor(256, 576)), FAKE, 0, None) == -6
+    assert lib.nvfp4_gemm_nt_static(C.byref(_tensor(256, 544)), C.byref(_tensor(256, 544)), FAKE, 0, None) == -2
+    assert lib.nvfp4_gemm_nt_static(C.byref(_tensor(256, 512, outer=1)), C.byref(ok), FAKE, 0, None) == -3
+    big = [(M, N, K) for (M, N, K) in ((3072, 3072, 65536), (2304, 4096, 65536), (1536, 8192, 32768), (4096, 3072, 262144))
+           if B.workspace_bytes(B.OP_GEMM, M, K, N) > B.STATIC_SCRATCH_BYTES]
+    assert big, "no candidate shape exceeds the static scratch array any more: extend the list"
+    for M, N, K in big:
+        assert lib.nvfp4_gemm_nt_static(C.byref(_tensor(M, K)), C.byref(_tensor(N, K)), FAKE, 0, None) == B.ERR_SCRATCH
+    assert b"static" in lib.nvfp4_strerror(B.ERR_SCRATCH)
+    header = open(os.path.join(ROOT, "include", "tjnvfp4.h")).read()
+    assert "#define NVFP4_STATIC_SCRATCH_BYTES (64u << 20)" in header and B.STATIC_SCRATCH_BYTES == 64 << 20
