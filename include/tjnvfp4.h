@@ -104,8 +104,11 @@ typedef struct nvfp4_qcfg {
 /*
  * Quantize (Sec. 2.1-2.2).  src is a bf16 [R x C] row-major device array (NVFP4_SRC_BF16) or a HOST pointer to an
  * nvfp4_tensor describing an [R x C] operand (NVFP4_SRC_NVFP4, re-quantization of Sec. 2.3's X_hat / W_hat, which
- * starts from the FP32 value code*scale*gscale).  axis 0: groups run along C, out describes [R x C] (K = C).
- * axis 1: groups run along R (16 x 1 groups), out describes the transpose [C x R] (K = R).
+ * starts from the FP32 value code*scale*gscale; axis 1 only; the source may be in either outer mode).
+ * axis 0: groups run along C, out describes [R x C] (K = C).
+ * axis 1: groups run along R (16 x 1 groups), out describes the transpose [C x R] (K = R); a bf16 source needs
+ * C % 8 == 0.  cfg->outer_mode is the outer group of the OUTPUT: the whole tensor, or 128 consecutive elements of
+ * its K axis (then K % 128 == 0 and no maximum is needed: the call is a single pass over src).
  * In TENSOR mode the tensor maximum is taken from cfg->amax_in, else from src->amax_deq (NVFP4 source), else by a
  * reduction pass over src.  Errors: NULL, SHAPE, ENUM, WORKSPACE, ALIGN, MISMATCH.
  */
@@ -125,8 +128,11 @@ int nvfp4_quantize_dual(const void *src, int64_t R, int64_t C, const nvfp4_qcfg 
 /*
  * Out[M x N] = A[M x K] * B[N x K]^T on two quantized operands grouped along K (Sec. 2.3: all three products take
  * this form).  Products of dequantized 16-bit values are exact; accumulation is FP32; the outer scales multiply
- * the accumulator at the end; Out is row-major bf16 or f32.  Both operands must be in TENSOR outer mode.
- * Limits: A->K == B->K, K % 64 == 0 and K <= 2^22 (SHAPE otherwise); any M = A->rows, N = B->rows.  ws: at least
+ * the accumulator at the end (TENSOR mode), or - with the paper's 1 x 128 outer blocks - the sum over each 128-k
+ * block is multiplied by the two blocks' FP32 scales before it joins the total; Out is row-major bf16 or f32.  Both
+ * operands must be in the same outer mode (MISMATCH otherwise).
+ * Limits: A->K == B->K, K % 64 == 0 (K % 128 == 0 in BLOCK128 mode) and K <= 2^22 (SHAPE otherwise); any M = A->rows,
+ * N = B->rows.  ws: at least
  * nvfp4_workspace_bytes(NVFP4_OP_GEMM, M, K, N, 0) bytes (0 for most shapes; FP32 partial sums when the planner
  * splits the reduction).  Errors: NULL, SHAPE, ENUM, WORKSPACE, ALIGN, MISMATCH.
  */
@@ -148,7 +154,10 @@ int nvfp4_gemm_nt_static(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out
 /*
  * Forward (Sec. 2.3, first line): quantizes X [N x D] and W [C x D] (bf16, round-to-nearest, groups along D) into
  * Xq_ctx / Wq_ctx, which the caller keeps for the backward calls, and writes Y [N x C].
- * Limits: D % 64 == 0 and D <= 2^22 (D is the reduction length); any N, C.  X, W, Y 16-byte aligned.
+ * outer_mode: outer group of both operands (NVFP4_OUTER_TENSOR: two maximum passes precede the quantizers;
+ * NVFP4_OUTER_BLOCK128: the paper's 1 x 128 blocks, single pass).  The backward calls follow the contexts' mode.
+ * Limits: D % 64 == 0 (D % 128 == 0 in BLOCK128 mode) and D <= 2^22 (D is the reduction length); any N, C.  X, W, Y
+ * 16-byte aligned.
  */
 int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t C,
                      void *Y, int out_dtype, nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx,
@@ -165,8 +174,7 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
 /*
  * Weight gradient (Sec. 2.3, third line): dW [C x D] = Q5_S(dY^T) x Q6_S(X_hat); both operands re-grouped along N
  * with stochastic rounding.  Streams: tensor ids layer_id*8+5 and +6.
- * Limits: N % 64 == 0 and N <= 2^22 (reduction length); C % 8 == 0 (128-bit loads along the rows of dY);
- * D % 16 == 0.
+ * Limits: N % 64 == 0 (N % 128 == 0 in BLOCK128 mode) and N <= 2^22 (reduction length); C % 8 == 0; D % 16 == 0.
  */
 int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C,
                         void *dW, int out_dtype, uint64_t seed, uint32_t layer_id,
@@ -176,7 +184,8 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
  * Both gradients of one layer in one call (Sec. 2.3, second and third line).  Same results, byte for byte, as
  * nvfp4_linear_bwd_dx followed by nvfp4_linear_bwd_dw with the same seed and layer_id, but dY is read once for its
  * maximum and once more for both of its quantizations (Q3 row-wise and Q5 column-wise leave one kernel).
- * Limits: C % 64 == 0, N % 64 == 0, both <= 2^22 (each is the reduction length of one product); D % 16 == 0.
+ * Limits: C % 64 == 0, N % 64 == 0 (% 128 in BLOCK128 mode), both <= 2^22 (each is the reduction length of one
+ * product); D % 16 == 0.  In BLOCK128 mode dY is read once per operand (no maximum pass, no fused quantizer).
  */
 int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx,
                      int64_t N, int64_t D, int64_t C, void *dX, void *dW, int out_dtype,
@@ -188,9 +197,9 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
  */
 size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_mode);
 
-/* Launch configuration nvfp4_gemm_nt uses for an [M x K] * [N x K]^T product: workgroup tile (rows x columns of the
+/* Launch configuration nvfp4_gemm_nt uses for an [M x K] * [N x K]^T product of operands in outer_mode: workgroup tile (rows x columns of the
  * output) and the number of K splits (> 1 means FP32 partials in ws plus a reduction kernel).  Host-only helper. */
-int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, int *tile_m, int *tile_n, int *split);
+int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, int outer_mode, int *tile_m, int *tile_n, int *split);
 
 /* Tensor maximum of |x| of a bf16 device array of n elements (n % 8 == 0) into amax_out (device [1]): the max |X| of
  * Sec. 2.2's S_global = max |X| / (448 * 6) for a per-tensor outer group.  ws: nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE, ..). */

@@ -77,7 +77,7 @@ def lib():
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
         L.nvfp4_gemm_plan.restype = i32
-        L.nvfp4_gemm_plan.argtypes = [i64, i64, i64, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.nvfp4_gemm_plan.argtypes = [i64, i64, i64, i32, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.nvfp4_amax_bf16.restype = i32
         L.nvfp4_amax_bf16.argtypes = [vp, i64, vp, vp, sz, vp]
         L.nvfp4_stream_key.restype = u64
@@ -148,10 +148,10 @@ def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
     return torch.empty((max(int(nbytes), 16),), dtype=torch.uint8, device=device)
 
 
-def gemm_plan(M: int, N: int, K: int):
-    """(tile rows, tile columns, K splits) nvfp4_gemm_nt will use for this shape."""
+def gemm_plan(M: int, N: int, K: int, outer: int = OUTER_TENSOR):
+    """(tile rows, tile columns, K splits) nvfp4_gemm_nt will use for this shape and outer mode."""
     a, b, c = C.c_int(), C.c_int(), C.c_int()
-    _check(lib().nvfp4_gemm_plan(M, N, K, C.byref(a), C.byref(b), C.byref(c)), "nvfp4_gemm_plan")
+    _check(lib().nvfp4_gemm_plan(M, N, K, outer, C.byref(a), C.byref(b), C.byref(c)), "nvfp4_gemm_plan")
     return a.value, b.value, c.value
 
 
@@ -235,7 +235,7 @@ def gemm_nt(A: NVFP4Tensor, B: NVFP4Tensor, out_dtype: int = OUT_BF16, out: Opti
     if out is None:
         out = _out_tensor(A.rows, B.rows, out_dtype, dev)
     if ws is None:
-        ws = alloc_workspace(workspace_bytes(OP_GEMM, A.rows, A.K, B.rows), dev)
+        ws = alloc_workspace(workspace_bytes(OP_GEMM, A.rows, A.K, B.rows, A.outer), dev)
     ca, cb = A.c_struct(), B.c_struct()
     rc = lib().nvfp4_gemm_nt(C.byref(ca), C.byref(cb), _ptr(out), out_dtype, _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_gemm_nt")
@@ -286,7 +286,7 @@ def linear_bwd_dx(dY: torch.Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, o
     dev = dY.device
     dX = _out_tensor(N, D, out_dtype, dev) if dX is None else dX
     _check_out(dX, (N, D), out_dtype, "dX")
-    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DX, N, D, Cc), dev) if ws is None else ws
+    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DX, N, D, Cc, Wq.outer), dev) if ws is None else ws
     cw = Wq.c_struct()
     rc = lib().nvfp4_linear_bwd_dx(_ptr(dY), C.byref(cw), N, D, Cc, _ptr(dX), out_dtype, seed, layer_id,
                                    _ptr(ws), ws.numel(), _stream())
@@ -302,7 +302,7 @@ def linear_bwd_dw(dY: torch.Tensor, Xq: NVFP4Tensor, seed: int, layer_id: int, o
     dev = dY.device
     dW = _out_tensor(Cc, D, out_dtype, dev) if dW is None else dW
     _check_out(dW, (Cc, D), out_dtype, "dW")
-    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DW, N, D, Cc), dev) if ws is None else ws
+    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DW, N, D, Cc, Xq.outer), dev) if ws is None else ws
     cx = Xq.c_struct()
     rc = lib().nvfp4_linear_bwd_dw(_ptr(dY), C.byref(cx), N, D, Cc, _ptr(dW), out_dtype, seed, layer_id,
                                    _ptr(ws), ws.numel(), _stream())
@@ -321,7 +321,7 @@ def linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, la
     dW = _out_tensor(Cc, D, out_dtype, dev) if dW is None else dW
     _check_out(dX, (N, D), out_dtype, "dX")
     _check_out(dW, (Cc, D), out_dtype, "dW")
-    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD, N, D, Cc), dev) if ws is None else ws
+    ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD, N, D, Cc, Xq.outer), dev) if ws is None else ws
     cx, cw = Xq.c_struct(), Wq.c_struct()
     rc = lib().nvfp4_linear_bwd(_ptr(dY), C.byref(cx), C.byref(cw), N, D, Cc, _ptr(dX), _ptr(dW), out_dtype, seed,
                                 layer_id, _ptr(ws), ws.numel(), _stream())

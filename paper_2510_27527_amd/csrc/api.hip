@@ -51,10 +51,15 @@ struct Carver {
 };
 
 size_t partials_bytes() { return align_up(sizeof(float) * kMaxAmaxPartials); }
-size_t packed_bytes(int64_t rows, int64_t K)
+size_t gscale_bytes(int64_t rows, int64_t K, int outer)
 {
-    return align_up((size_t)(rows * K / 2)) + align_up((size_t)(rows * K / 16)) + align_up(sizeof(float));
+    return outer == NVFP4_OUTER_BLOCK128 ? sizeof(float) * (size_t)(rows * (K / 128)) : sizeof(float);
 }
+size_t packed_bytes(int64_t rows, int64_t K, int outer)
+{
+    return align_up((size_t)(rows * K / 2)) + align_up((size_t)(rows * K / 16)) + align_up(gscale_bytes(rows, K, outer));
+}
+bool valid_outer(int outer) { return outer == NVFP4_OUTER_TENSOR || outer == NVFP4_OUTER_BLOCK128; }
 
 int check_shape(int64_t rows, int64_t K, int outer)
 {
@@ -79,12 +84,12 @@ int check_tensor_ptrs(const nvfp4_tensor *t)
 constexpr int64_t kMaxReduction = (int64_t)1 << 22;
 int check_reduction(int64_t K) { return (K % 64 != 0 || K > kMaxReduction) ? NVFP4_ERR_SHAPE : NVFP4_OK; }
 
-// a gemm operand must be a finished TENSOR-mode operand with K % 64 == 0
+// a gemm operand must be a finished operand with K % 64 == 0 (K % 128 == 0 with 1 x 128 outer blocks)
 int check_gemm_operand(const nvfp4_tensor *t)
 {
     int rc = check_tensor_ptrs(t);
     if (rc) return rc;
-    if (t->outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;
+    if (!valid_outer(t->outer_mode)) return NVFP4_ERR_ENUM;
     rc = check_shape(t->rows, t->K, t->outer_mode);
     if (rc) return rc;
     return check_reduction(t->K);
@@ -126,7 +131,6 @@ int plan_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis,
     if (src_kind == NVFP4_SRC_BF16) {
         if (!aligned16(src)) return NVFP4_ERR_ALIGN;
         if (axis == 1 && C % 8 != 0) return NVFP4_ERR_SHAPE;           // 128-bit loads along C
-        if (axis == 1 && pl->outer == NVFP4_OUTER_BLOCK128) return NVFP4_ERR_ENUM;
         pl->need_partials = pl->outer == NVFP4_OUTER_TENSOR && cfg->amax_in == nullptr;
     } else {
         const nvfp4_tensor *s = static_cast<const nvfp4_tensor *>(src);
@@ -135,10 +139,10 @@ int plan_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis,
         if (s->rows != R || s->K != C) return NVFP4_ERR_MISMATCH;
         rc = check_shape(R, C, s->outer_mode);
         if (rc) return rc;
-        // provided: TENSOR-mode source re-grouped along the other axis in TENSOR mode (Q4, Q6)
-        if (axis != 1 || s->outer_mode != NVFP4_OUTER_TENSOR || pl->outer != NVFP4_OUTER_TENSOR)
-            return NVFP4_ERR_ENUM;
-        if (!cfg->amax_in && !s->amax_deq) return NVFP4_ERR_NULL;
+        // provided: a packed source re-grouped along its other axis (Q4, Q6), in either outer mode on either side
+        if (axis != 1) return NVFP4_ERR_ENUM;
+        if (s->outer_mode != NVFP4_OUTER_TENSOR && s->outer_mode != NVFP4_OUTER_BLOCK128) return NVFP4_ERR_ENUM;
+        if (pl->outer == NVFP4_OUTER_TENSOR && !cfg->amax_in && !s->amax_deq) return NVFP4_ERR_NULL;
         pl->need_partials = false;
     }
     return NVFP4_OK;
@@ -185,7 +189,7 @@ int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nv
                          : launch_quant_col_bf16(src, pl.R, pl.C, p, o, st);
     } else {
         const nvfp4_tensor *s = static_cast<const nvfp4_tensor *>(src);
-        p.amax_scalar = cfg->amax_in ? cfg->amax_in : s->amax_deq;
+        p.amax_scalar = pl.outer == NVFP4_OUTER_TENSOR ? (cfg->amax_in ? cfg->amax_in : s->amax_deq) : nullptr;
         o.amax_deq = nullptr;
         PackedSrc ps{s->codes, s->scales, s->gscale, s->outer_mode};
         e = launch_requant_col(ps, pl.R, pl.C, p, o, st);
@@ -219,8 +223,8 @@ int run_quantize_row_pair(const void *src0, const QuantPlan &pl0, nvfp4_tensor *
                           hipStream_t st)
 {
     const bool pairable = pl0.src_kind == NVFP4_SRC_BF16 && pl1.src_kind == NVFP4_SRC_BF16 && pl0.axis == 0 &&
-                          pl1.axis == 0 && pl0.outer == NVFP4_OUTER_TENSOR && pl1.outer == NVFP4_OUTER_TENSOR &&
-                          cfg->amax_in == nullptr && pl0.R * pl0.C > 0 && pl1.R * pl1.C > 0;
+                          pl1.axis == 0 && pl0.outer == pl1.outer && cfg->amax_in == nullptr && pl0.R * pl0.C > 0 &&
+                          pl1.R * pl1.C > 0;
     if (!pairable) {
         const int rc = run_quantize(src0, pl0, cfg, out0, partials0, st);
         return rc ? rc : run_quantize(src1, pl1, cfg, out1, partials1, st);
@@ -231,10 +235,17 @@ int run_quantize_row_pair(const void *src0, const QuantPlan &pl0, nvfp4_tensor *
     if (pl0.rounding != NVFP4_ROUND_RTN) o0.amax_deq = o1.amax_deq = nullptr;
     stamp(out0, pl0);
     stamp(out1, pl1);
-    launch_amax_partials_pair(src0, pl0.R * pl0.C, partials0, o0.amax_deq, &p0.npart, src1, pl1.R * pl1.C, partials1,
-                              o1.amax_deq, &p1.npart, st);
-    p0.amax_partials = partials0;
-    p1.amax_partials = partials1;
+    if (pl0.outer == NVFP4_OUTER_TENSOR) {
+        launch_amax_partials_pair(src0, pl0.R * pl0.C, partials0, o0.amax_deq, &p0.npart, src1, pl1.R * pl1.C, partials1,
+                                  o1.amax_deq, &p1.npart, st);
+        p0.amax_partials = partials0;
+        p1.amax_partials = partials1;
+    } else {
+        // 1 x 128 outer blocks: no maximum pass; the dequantized maximum (an atomic maximum over the workgroups) is
+        // only wanted by a later tensor-mode re-quantization and starts from zero
+        if (o0.amax_deq) launch_zero_scalar(o0.amax_deq, st);
+        if (o1.amax_deq) launch_zero_scalar(o1.amax_deq, st);
+    }
     const hipError_t e = launch_quant_row_bf16_pair(src0, pl0.R, pl0.C, p0, o0, src1, pl1.R, pl1.C, p1, o1, st);
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
@@ -245,9 +256,9 @@ int run_requant_pair(const nvfp4_tensor *s0, const QuantPlan &pl0, const nvfp4_q
                      hipStream_t st)
 {
     QuantParams p0 = params_of(pl0, c0), p1 = params_of(pl1, c1);
-    p0.amax_scalar = c0->amax_in ? c0->amax_in : s0->amax_deq;
-    p1.amax_scalar = c1->amax_in ? c1->amax_in : s1->amax_deq;
-    if (p0.rounding != p1.rounding || p0.scale_up != p1.scale_up) {
+    p0.amax_scalar = pl0.outer == NVFP4_OUTER_TENSOR ? (c0->amax_in ? c0->amax_in : s0->amax_deq) : nullptr;
+    p1.amax_scalar = pl1.outer == NVFP4_OUTER_TENSOR ? (c1->amax_in ? c1->amax_in : s1->amax_deq) : nullptr;
+    if (p0.rounding != p1.rounding || p0.scale_up != p1.scale_up || p0.outer != p1.outer) {
         const int rc = run_quantize(s0, pl0, c0, out0, nullptr, st);
         return rc ? rc : run_quantize(s1, pl1, c1, out1, nullptr, st);
     }
@@ -262,8 +273,9 @@ int run_requant_pair(const nvfp4_tensor *s0, const QuantPlan &pl0, const nvfp4_q
 int run_gemm(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *ws, size_t ws_bytes,
              hipStream_t st)
 {
-    GemmOperand a{A->codes, A->scales, A->gscale, A->rows};
-    GemmOperand b{B->codes, B->scales, B->gscale, B->rows};
+    const int outer = A->outer_mode == NVFP4_OUTER_BLOCK128 ? 1 : 0;
+    GemmOperand a{A->codes, A->scales, A->gscale, A->rows, outer};
+    GemmOperand b{B->codes, B->scales, B->gscale, B->rows, outer};
     const hipError_t e = launch_gemm_nt(a, b, A->K, Out, out_dtype == NVFP4_OUT_F32, ws, ws_bytes, st);
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
@@ -296,15 +308,15 @@ int static_scratch(void **out)
 }
 
 // carve a temporary operand [rows x K] out of the workspace
-bool carve_tensor(Carver &cv, int64_t rows, int64_t K, nvfp4_tensor *t)
+bool carve_tensor(Carver &cv, int64_t rows, int64_t K, int outer, nvfp4_tensor *t)
 {
     t->codes = static_cast<uint8_t *>(cv.take((size_t)(rows * K / 2)));
     t->scales = static_cast<uint8_t *>(cv.take((size_t)(rows * K / 16)));
-    t->gscale = static_cast<float *>(cv.take(sizeof(float)));
+    t->gscale = static_cast<float *>(cv.take(gscale_bytes(rows, K, outer)));
     t->amax_deq = nullptr;
     t->rows = rows;
     t->K = K;
-    t->outer_mode = NVFP4_OUTER_TENSOR;
+    t->outer_mode = outer;
     t->reserved = 0;
     return t->codes && t->scales && t->gscale;
 }
@@ -338,30 +350,32 @@ uint64_t nvfp4_stream_key(uint64_t seed, uint32_t tensor_id) { return stream_key
 
 size_t nvfp4_workspace_bytes(int op, int64_t N, int64_t D, int64_t C, int outer_mode)
 {
-    (void)outer_mode;
-    if (N < 0 || D < 0 || C < 0) return 0;
+    if (N < 0 || D < 0 || C < 0 || !valid_outer(outer_mode)) return 0;
+    const int o = outer_mode;
     switch (op) {
         case NVFP4_OP_QUANTIZE: return partials_bytes();
-        case NVFP4_OP_GEMM: return align_up(gemm_workspace_bytes(N, C, D));
-        case NVFP4_OP_LINEAR_FWD: return 2 * partials_bytes() + align_up(gemm_workspace_bytes(N, C, D));
+        case NVFP4_OP_GEMM: return align_up(gemm_workspace_bytes(N, C, D, o));
+        case NVFP4_OP_LINEAR_FWD: return 2 * partials_bytes() + align_up(gemm_workspace_bytes(N, C, D, o));
         case NVFP4_OP_LINEAR_BWD_DX:
-            return partials_bytes() + packed_bytes(N, C) + packed_bytes(D, C) + align_up(gemm_workspace_bytes(N, D, C));
+            return partials_bytes() + packed_bytes(N, C, o) + packed_bytes(D, C, o) + align_up(gemm_workspace_bytes(N, D, C, o));
         case NVFP4_OP_LINEAR_BWD_DW:
-            return partials_bytes() + packed_bytes(C, N) + packed_bytes(D, N) + align_up(gemm_workspace_bytes(C, D, N));
+            return partials_bytes() + packed_bytes(C, N, o) + packed_bytes(D, N, o) + align_up(gemm_workspace_bytes(C, D, N, o));
         case NVFP4_OP_LINEAR_BWD: {
-            const size_t g1 = align_up(gemm_workspace_bytes(N, D, C)), g2 = align_up(gemm_workspace_bytes(C, D, N));
-            return partials_bytes() + align_up(sizeof(float)) + packed_bytes(N, C) + packed_bytes(D, C) +
-                   packed_bytes(C, N) + packed_bytes(D, N) + (g1 > g2 ? g1 : g2);
+            const size_t g1 = align_up(gemm_workspace_bytes(N, D, C, o)), g2 = align_up(gemm_workspace_bytes(C, D, N, o));
+            return partials_bytes() + align_up(sizeof(float)) + packed_bytes(N, C, o) + packed_bytes(D, C, o) +
+                   packed_bytes(C, N, o) + packed_bytes(D, N, o) + (g1 > g2 ? g1 : g2);
         }
         default: return 0;
     }
 }
 
-int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, int *tile_m, int *tile_n, int *split)
+int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, int outer_mode, int *tile_m, int *tile_n, int *split)
 {
     if (!tile_m || !tile_n || !split) return NVFP4_ERR_NULL;
+    if (!valid_outer(outer_mode)) return NVFP4_ERR_ENUM;
     if (M < 0 || N < 0 || K < 0 || K % 64 != 0) return NVFP4_ERR_SHAPE;
-    gemm_plan(M, N, K, tile_m, tile_n, split);
+    if (outer_mode == NVFP4_OUTER_BLOCK128 && K % 128 != 0) return NVFP4_ERR_SHAPE;
+    gemm_plan(M, N, K, outer_mode, tile_m, tile_n, split);
     return NVFP4_OK;
 }
 
@@ -419,8 +433,8 @@ int nvfp4_quantize_dual(const void *src, int64_t R, int64_t C, const nvfp4_qcfg 
     return launch_quant_dual_bf16(src, R, C, pr, orow, pc, ocol, st) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
-int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *ws, size_t ws_bytes,
-                  void *stream)
+// common validation of the two product entry points; *need = scratch bytes of the split reduction
+static int check_gemm_call(const nvfp4_tensor *A, const nvfp4_tensor *B, const void *Out, int out_dtype, size_t *need)
 {
     int rc = check_gemm_operand(A);
     if (rc) return rc;
@@ -428,23 +442,27 @@ int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int o
     if (rc) return rc;
     rc = check_out(Out, out_dtype);
     if (rc) return rc;
-    if (A->K != B->K) return NVFP4_ERR_MISMATCH;
+    if (A->K != B->K || A->outer_mode != B->outer_mode) return NVFP4_ERR_MISMATCH;
+    *need = gemm_workspace_bytes(A->rows, B->rows, A->K, A->outer_mode);
+    return NVFP4_OK;
+}
+
+int nvfp4_gemm_nt(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *ws, size_t ws_bytes,
+                  void *stream)
+{
+    size_t need = 0;
+    const int rc = check_gemm_call(A, B, Out, out_dtype, &need);
+    if (rc) return rc;
     if (ws && !aligned16(ws)) return NVFP4_ERR_ALIGN;
-    if (gemm_workspace_bytes(A->rows, B->rows, A->K) > 0 && (!ws || ws_bytes < gemm_workspace_bytes(A->rows, B->rows, A->K)))
-        return NVFP4_ERR_WORKSPACE;
+    if (need > 0 && (!ws || ws_bytes < need)) return NVFP4_ERR_WORKSPACE;
     return run_gemm(A, B, Out, out_dtype, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int nvfp4_gemm_nt_static(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out, int out_dtype, void *stream)
 {
-    int rc = check_gemm_operand(A);
+    size_t need = 0;
+    int rc = check_gemm_call(A, B, Out, out_dtype, &need);
     if (rc) return rc;
-    rc = check_gemm_operand(B);
-    if (rc) return rc;
-    rc = check_out(Out, out_dtype);
-    if (rc) return rc;
-    if (A->K != B->K) return NVFP4_ERR_MISMATCH;
-    const size_t need = gemm_workspace_bytes(A->rows, B->rows, A->K);
     if (need > kStaticScratchBytes) return NVFP4_ERR_SCRATCH;
     void *ws = nullptr;
     if (need > 0) {
@@ -459,7 +477,7 @@ int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t
                      void *stream)
 {
     if (!X || !W) return NVFP4_ERR_NULL;
-    if (outer_mode != NVFP4_OUTER_TENSOR) return NVFP4_ERR_ENUM;      // the products take tensor-mode operands
+    if (!valid_outer(outer_mode)) return NVFP4_ERR_ENUM;
     if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
     if (check_reduction(D)) return NVFP4_ERR_SHAPE;
     int rc = check_out(Y, out_dtype);
@@ -479,11 +497,22 @@ int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t
     Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
     float *part_x = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
     float *part_w = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
-    const size_t gbytes = gemm_workspace_bytes(N, C, D);
+    const size_t gbytes = gemm_workspace_bytes(N, C, D, outer_mode);
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
     rc = run_quantize_row_pair(X, px, Xq_ctx, part_x, W, pw, Wq_ctx, part_w, &cfg, st);
     if (rc) return rc;
     return run_gemm(Xq_ctx, Wq_ctx, Y, out_dtype, gws, gbytes, st);
+}
+
+// stochastic-rounding settings of backward quantizer Q<k> of a layer (k = 3..6), in the forward operands' outer mode
+static nvfp4_qcfg bwd_cfg(uint64_t seed, uint32_t layer_id, int k, int outer)
+{
+    nvfp4_qcfg c{};
+    c.rounding = NVFP4_ROUND_SR;
+    c.outer_mode = outer;
+    c.seed = seed;
+    c.tensor_id = layer_id * 8u + (uint32_t)k;
+    return c;
 }
 
 int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D, int64_t C, void *dX,
@@ -495,23 +524,18 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
     int rc = check_out(dX, out_dtype);
     if (rc) return rc;
     if (Wq_ctx->rows != C || Wq_ctx->K != D) return NVFP4_ERR_MISMATCH;
-    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD_DX, N, D, C, NVFP4_OUTER_TENSOR))
-        return NVFP4_ERR_WORKSPACE;
+    const int outer = Wq_ctx->outer_mode;
+    if (!valid_outer(outer)) return NVFP4_ERR_ENUM;
+    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD_DX, N, D, C, outer)) return NVFP4_ERR_WORKSPACE;
     if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
     Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
     float *part = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
     nvfp4_tensor dYq{}, Wq2{};
-    if (!carve_tensor(cv, N, C, &dYq) || !carve_tensor(cv, D, C, &Wq2)) return NVFP4_ERR_WORKSPACE;
-    const size_t gbytes = gemm_workspace_bytes(N, D, C);
+    if (!carve_tensor(cv, N, C, outer, &dYq) || !carve_tensor(cv, D, C, outer, &Wq2)) return NVFP4_ERR_WORKSPACE;
+    const size_t gbytes = gemm_workspace_bytes(N, D, C, outer);
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
 
-    nvfp4_qcfg c3{};
-    c3.rounding = NVFP4_ROUND_SR;
-    c3.outer_mode = NVFP4_OUTER_TENSOR;
-    c3.seed = seed;
-    c3.tensor_id = layer_id * 8u + 3u;
-    nvfp4_qcfg c4 = c3;
-    c4.tensor_id = layer_id * 8u + 4u;
+    nvfp4_qcfg c3 = bwd_cfg(seed, layer_id, 3, outer), c4 = bwd_cfg(seed, layer_id, 4, outer);
     QuantPlan p3{}, p4{};
     rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 0, &c3, &dYq, &p3);
     if (rc) return rc;
@@ -534,23 +558,18 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
     int rc = check_out(dW, out_dtype);
     if (rc) return rc;
     if (Xq_ctx->rows != N || Xq_ctx->K != D) return NVFP4_ERR_MISMATCH;
-    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD_DW, N, D, C, NVFP4_OUTER_TENSOR))
-        return NVFP4_ERR_WORKSPACE;
+    const int outer = Xq_ctx->outer_mode;
+    if (!valid_outer(outer)) return NVFP4_ERR_ENUM;
+    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD_DW, N, D, C, outer)) return NVFP4_ERR_WORKSPACE;
     if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
     Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
     float *part = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
     nvfp4_tensor dYq{}, Xq2{};
-    if (!carve_tensor(cv, C, N, &dYq) || !carve_tensor(cv, D, N, &Xq2)) return NVFP4_ERR_WORKSPACE;
-    const size_t gbytes = gemm_workspace_bytes(C, D, N);
+    if (!carve_tensor(cv, C, N, outer, &dYq) || !carve_tensor(cv, D, N, outer, &Xq2)) return NVFP4_ERR_WORKSPACE;
+    const size_t gbytes = gemm_workspace_bytes(C, D, N, outer);
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
 
-    nvfp4_qcfg c5{};
-    c5.rounding = NVFP4_ROUND_SR;
-    c5.outer_mode = NVFP4_OUTER_TENSOR;
-    c5.seed = seed;
-    c5.tensor_id = layer_id * 8u + 5u;
-    nvfp4_qcfg c6 = c5;
-    c6.tensor_id = layer_id * 8u + 6u;
+    nvfp4_qcfg c5 = bwd_cfg(seed, layer_id, 5, outer), c6 = bwd_cfg(seed, layer_id, 6, outer);
     QuantPlan p5{}, p6{};
     rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 1, &c5, &dYq, &p5);
     if (rc) return rc;
@@ -576,31 +595,29 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
     rc = check_out(dW, out_dtype);
     if (rc) return rc;
     if (Wq_ctx->rows != C || Wq_ctx->K != D || Xq_ctx->rows != N || Xq_ctx->K != D) return NVFP4_ERR_MISMATCH;
+    if (Wq_ctx->outer_mode != Xq_ctx->outer_mode) return NVFP4_ERR_MISMATCH;
+    const int outer = Xq_ctx->outer_mode;
+    if (!valid_outer(outer)) return NVFP4_ERR_ENUM;
     if (!aligned16(dY)) return NVFP4_ERR_ALIGN;
-    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD, N, D, C, NVFP4_OUTER_TENSOR))
-        return NVFP4_ERR_WORKSPACE;
+    if (!ws || ws_bytes < nvfp4_workspace_bytes(NVFP4_OP_LINEAR_BWD, N, D, C, outer)) return NVFP4_ERR_WORKSPACE;
     if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
     Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
     float *part = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
     float *amax = static_cast<float *>(cv.take(sizeof(float)));
     nvfp4_tensor q3{}, q4{}, q5{}, q6{};
-    if (!carve_tensor(cv, N, C, &q3) || !carve_tensor(cv, D, C, &q4) || !carve_tensor(cv, C, N, &q5) ||
-        !carve_tensor(cv, D, N, &q6))
+    if (!carve_tensor(cv, N, C, outer, &q3) || !carve_tensor(cv, D, C, outer, &q4) || !carve_tensor(cv, C, N, outer, &q5) ||
+        !carve_tensor(cv, D, N, outer, &q6))
         return NVFP4_ERR_WORKSPACE;
-    const size_t g1 = gemm_workspace_bytes(N, D, C), g2 = gemm_workspace_bytes(C, D, N);
+    const size_t g1 = gemm_workspace_bytes(N, D, C, outer), g2 = gemm_workspace_bytes(C, D, N, outer);
     const size_t gbytes = g1 > g2 ? g1 : g2;
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
 
     nvfp4_qcfg c[4];
-    for (int k = 0; k < 4; ++k) {
-        c[k] = nvfp4_qcfg{};
-        c[k].rounding = NVFP4_ROUND_SR;
-        c[k].outer_mode = NVFP4_OUTER_TENSOR;
-        c[k].seed = seed;
-        c[k].tensor_id = layer_id * 8u + 3u + (uint32_t)k;
+    for (int k = 0; k < 4; ++k) c[k] = bwd_cfg(seed, layer_id, 3 + k, outer);
+    if (outer == NVFP4_OUTER_TENSOR) {
+        c[0].amax_in = amax;     // Q3 and Q5 share the maximum of dY
+        c[2].amax_in = amax;
     }
-    c[0].amax_in = amax;     // Q3 and Q5 share the maximum of dY
-    c[2].amax_in = amax;
     QuantPlan p3{}, p4{}, p5{}, p6{};
     rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 0, &c[0], &q3, &p3);
     if (rc) return rc;
@@ -612,21 +629,29 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
     if (rc) return rc;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (N > 0 && C > 0) {
-        // every workgroup of the quantizer reduces the partial maxima itself: no launch in between
-        const int npart = launch_amax_partials(dY, N * C, part, nullptr, st);
-        QuantParams pr{}, pc{};
-        pr.rounding = pc.rounding = 1;
-        pr.scale_up = pc.scale_up = 1;
-        pr.amax_partials = pc.amax_partials = part;
-        pr.npart = pc.npart = npart;
-        const uint64_t k3 = stream_key(seed, c[0].tensor_id), k5 = stream_key(seed, c[2].tensor_id);
-        pr.k0 = (uint32_t)k3; pr.k1 = (uint32_t)(k3 >> 32);
-        pc.k0 = (uint32_t)k5; pc.k1 = (uint32_t)(k5 >> 32);
-        QuantOut orow{q3.codes, q3.scales, q3.gscale, nullptr}, ocol{q5.codes, q5.scales, q5.gscale, nullptr};
-        if (launch_quant_dual_bf16(dY, N, C, pr, orow, pc, ocol, st) != hipSuccess) return NVFP4_ERR_HIP;
+    if (outer == NVFP4_OUTER_TENSOR) {
+        if (N > 0 && C > 0) {
+            // every workgroup of the quantizer reduces the partial maxima itself: no launch in between
+            const int npart = launch_amax_partials(dY, N * C, part, nullptr, st);
+            QuantParams pr{}, pc{};
+            pr.rounding = pc.rounding = 1;
+            pr.scale_up = pc.scale_up = 1;
+            pr.amax_partials = pc.amax_partials = part;
+            pr.npart = pc.npart = npart;
+            const uint64_t k3 = stream_key(seed, c[0].tensor_id), k5 = stream_key(seed, c[2].tensor_id);
+            pr.k0 = (uint32_t)k3; pr.k1 = (uint32_t)(k3 >> 32);
+            pc.k0 = (uint32_t)k5; pc.k1 = (uint32_t)(k5 >> 32);
+            QuantOut orow{q3.codes, q3.scales, q3.gscale, nullptr}, ocol{q5.codes, q5.scales, q5.gscale, nullptr};
+            if (launch_quant_dual_bf16(dY, N, C, pr, orow, pc, ocol, st) != hipSuccess) return NVFP4_ERR_HIP;
+        }
+        q3.rows = N; q3.K = C; q5.rows = C; q5.K = N;
+    } else {
+        // 1 x 128 outer blocks: no maximum pass at all; dY is read once per operand, each a single pass
+        rc = run_quantize(dY, p3, &c[0], &q3, nullptr, st);
+        if (rc) return rc;
+        rc = run_quantize(dY, p5, &c[2], &q5, nullptr, st);
+        if (rc) return rc;
     }
-    q3.rows = N; q3.K = C; q5.rows = C; q5.K = N;
     rc = run_requant_pair(Wq_ctx, p4, &c[1], &q4, Xq_ctx, p6, &c[3], &q6, st);
     if (rc) return rc;
     rc = run_gemm(&q3, &q4, dX, out_dtype, gws, gbytes, st);

@@ -27,9 +27,10 @@ __device__ __forceinline__ float4 ld4(const float *p)
 // sum the split-K partials in split order, scale, convert
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *__restrict__ part, int split,
                                                                  int64_t mn, const float *a_gscale,
-                                                                 const float *b_gscale, void *out, int out_f32)
+                                                                 const float *b_gscale, int outer, void *out, int out_f32)
 {
-    const float alpha = a_gscale[0] * b_gscale[0] * 256.0f;
+    // block mode: the partial sums already carry the outer scales
+    const float alpha = outer ? 256.0f : a_gscale[0] * b_gscale[0] * 256.0f;
     const int64_t i4 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
     if (i4 >= mn) return;
     if ((mn & 3) == 0) {
@@ -71,7 +72,7 @@ constexpr int kNumCU = 256;
 
 struct Plan { int tile; int split; int chunks_per_split; };
 
-Plan make_plan(int64_t M, int64_t N, int64_t K)
+Plan make_plan(int64_t M, int64_t N, int64_t K, int outer)
 {
     const int64_t chunks = K / 64;
     Plan best{3, 1, (int)chunks};
@@ -79,12 +80,14 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
     double best_t = 1e300;
     for (int t = 0; t < kNumTiles; ++t) {
         if (t == 4 && K % 256 != 0) continue;
+        if (t == 0 && outer) continue;                      // block mode keeps two accumulator sets: at most 2 x 4 tiles per wave
         const int64_t bm = 64 * kTiles[t].tm, bn = 64 * kTiles[t].tn;
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         for (int split = 1; split <= 16; ++split) {
             if (split > 1 && chunks / split < 8) break;
             int64_t cps = (chunks + split - 1) / split;
             if (chunks % 4 == 0) cps = (cps + 3) / 4 * 4;                       // splits on 256-k boundaries
+            else if (outer) cps = (cps + 1) / 2 * 2;                            // block mode: on 128-k boundaries
             if (split > 1 && (chunks + cps - 1) / cps != split) continue;      // same launch as a smaller split
             const int64_t wgs = tiles * split;
             const double stages = (double)((cps + kNC - 1) / kNC);
@@ -93,7 +96,8 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
             const int64_t conc = per_cu < kTiles[t].occupancy ? per_cu : kTiles[t].occupancy;
             const double slow = conc == 1 ? 1.0 : conc == 2 ? 1.75 : 2.35;
             const int64_t waves = (wgs + kNumCU * conc - 1) / (kNumCU * conc);
-            double time = (double)waves * (stages * kTiles[t].t_stage * slow + kTiles[t].t_fixed);
+            // block mode: the per-block rescale of the accumulators makes a stage about a third longer
+            double time = (double)waves * (stages * kTiles[t].t_stage * (outer ? 1.35 : 1.0) * slow + kTiles[t].t_fixed);
             if (split > 1) time += 4.0 + (double)(split + 1) * (double)(M * N) * 4.0 / 3.5e6;   // partials out and back in
             if (time < best_t) { best_t = time; best = Plan{t, split, (int)cps}; }
         }
@@ -103,17 +107,17 @@ Plan make_plan(int64_t M, int64_t N, int64_t K)
 
 }  // namespace
 
-void gemm_plan(int64_t M, int64_t N, int64_t K, int *bm, int *bn, int *split)
+void gemm_plan(int64_t M, int64_t N, int64_t K, int outer, int *bm, int *bn, int *split)
 {
-    const Plan p = make_plan(M, N, K);
+    const Plan p = make_plan(M, N, K, outer);
     *bm = 64 * kTiles[p.tile].tm;
     *bn = 64 * kTiles[p.tile].tn;
     *split = p.split;
 }
 
-size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int outer)
 {
-    const Plan p = make_plan(M, N, K);
+    const Plan p = make_plan(M, N, K, outer);
     return p.split > 1 ? (size_t)p.split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
@@ -129,7 +133,8 @@ hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K,
                            static_cast<uint16_t *>(out), n16);
         return hipGetLastError();
     }
-    Plan p = make_plan(M, N, K);
+    const int outer = A.outer;
+    Plan p = make_plan(M, N, K, outer);
     if (p.split > 1 && (ws == nullptr || ws_bytes < (size_t)p.split * M * N * sizeof(float))) return hipErrorInvalidValue;
     GemmArgs g;
     g.a_codes = A.codes; g.a_scales = A.scales; g.a_gscale = A.gscale;
@@ -140,25 +145,26 @@ hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K,
     g.tiles_n = (int)((N + bn - 1) / bn);
     g.chunks_per_split = p.chunks_per_split;
     g.out_f32 = out_f32;
+    g.outer = outer;
     const int64_t chunks = K / 64;
     const int split = p.split > 1 ? (int)((chunks + p.chunks_per_split - 1) / p.chunks_per_split) : 1;
     g.out = split > 1 ? ws : out;
     dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)split);
     // K a multiple of 256 with splits on 256-boundaries: scale bytes are fetched 16 per row
     const bool ps = K % 256 == 0 && p.chunks_per_split % 4 == 0;
-    hipError_t e;
-    if (ps)
-        e = split > 1 ? launch_gemm_inst_ps1_out2(p.tile, g, grid, st)
-            : out_f32 ? launch_gemm_inst_ps1_out1(p.tile, g, grid, st) : launch_gemm_inst_ps1_out0(p.tile, g, grid, st);
-    else
-        e = split > 1 ? launch_gemm_inst_ps0_out2(p.tile, g, grid, st)
-            : out_f32 ? launch_gemm_inst_ps0_out1(p.tile, g, grid, st) : launch_gemm_inst_ps0_out0(p.tile, g, grid, st);
+    typedef hipError_t (*InstFn)(int, const GemmArgs &, dim3, hipStream_t);
+    static const InstFn inst[2][2][3] = {
+        {{launch_gemm_inst_ps0_out0_outer0, launch_gemm_inst_ps0_out1_outer0, launch_gemm_inst_ps0_out2_outer0},
+         {launch_gemm_inst_ps1_out0_outer0, launch_gemm_inst_ps1_out1_outer0, launch_gemm_inst_ps1_out2_outer0}},
+        {{launch_gemm_inst_ps0_out0_outer1, launch_gemm_inst_ps0_out1_outer1, launch_gemm_inst_ps0_out2_outer1},
+         {launch_gemm_inst_ps1_out0_outer1, launch_gemm_inst_ps1_out1_outer1, launch_gemm_inst_ps1_out2_outer1}}};
+    hipError_t e = inst[outer ? 1 : 0][ps ? 1 : 0][split > 1 ? 2 : (out_f32 ? 1 : 0)](p.tile, g, grid, st);
     if (e != hipSuccess) return e;
     if (split > 1) {
         const int64_t mn = M * N;
         const unsigned rgrid = (unsigned)((mn + (int64_t)kThreads * 4 - 1) / ((int64_t)kThreads * 4));
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3(rgrid), dim3(kThreads), 0, st,
-                           reinterpret_cast<const float *>(ws), split, mn, A.gscale, B.gscale, out, out_f32);
+                           reinterpret_cast<const float *>(ws), split, mn, A.gscale, B.gscale, outer, out, out_f32);
         e = hipGetLastError();
     }
     return e;

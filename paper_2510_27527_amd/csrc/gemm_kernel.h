@@ -60,18 +60,27 @@ __device__ __forceinline__ void lds_dma4(const void *base, uint32_t off, uint32_
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
 }
 
+// a wave-uniform pointer the compiler computed in vector registers, moved to scalar registers
+__device__ __forceinline__ const void *to_scalar(const void *p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo);
+}
+
 __device__ __forceinline__ uint32_t pick(uint4 v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
 // Epilogue of both product kernels: outer scales, conversion, stores.
 // SWAP (bf16 output): a lane holds one output row (m = lane % 32) and, per 32 x 32 block, four runs of four consecutive
 // columns; otherwise lanes run along the columns and accumulator element e sits in row 8 * (e / 4) + 4 * (lane / 32) + e % 4.
-template <int TM, int TN, int OUT, bool SWAP>
+template <int TM, int TN, int OUT, bool SWAP, int OUTER>
 __device__ __forceinline__ void store_tile(float16_t (&acc)[TM][TN], const GemmArgs &g, int64_t m0, int64_t n0, int wm, int wn,
                                            int lr, int kg)
 {
     constexpr bool SPLIT = OUT == 2;
     float alpha = 1.0f;
-    if (!SPLIT) alpha = g.a_gscale[0] * g.b_gscale[0] * 256.0f;
+    // tensor mode: both outer scales and the 2^8 of the FP16 pre-scale; block mode: the outer scales are already in
+    if (!SPLIT) alpha = OUTER == 0 ? g.a_gscale[0] * g.b_gscale[0] * 256.0f : 256.0f;
     if (SWAP) {
         // a lane holds one output row (m = lane % 32) and, per 32 x 32 block, four runs of four consecutive columns
         // (n = 8 * (e / 4) + 4 * (lane / 32) + e % 4): each run leaves as one 8-byte store
@@ -145,17 +154,27 @@ struct OpFrags {
     half8_t a[TM], b[TN];
 };
 
-template <int TM, int TN, int NC, int OUT, bool PS>   // OUT: 0 bf16, 1 f32, 2 raw f32 split-K partial
-__global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kernel(GemmArgs g)
+// OUTER = 1: operands with one FP32 outer scale per row and 128 k (the paper's 1 x 128 outer block, Sec. 2.2).  A
+// pipeline stage is exactly one outer block, so each stage accumulates into a fresh set of accumulators (its first
+// MFMA takes zero as addend) and at its end  total += stage_sum * S_A[m, kb] * S_B[n, kb]  in FP32 (two vector
+// instructions per accumulator element and stage, which is why this mode keeps at most 2 x 4 tiles per wave).  The
+// outer scales of a stage travel global -> LDS with the same direct copies, one float per row, into a ring of four.
+template <int TM, int TN, int NC, int OUT, bool PS, int OUTER>   // OUT: 0 bf16, 1 f32, 2 raw f32 split-K partial
+__global__ __launch_bounds__(kThreads, (TM * TN * (OUTER + 1) >= 8 ? 1 : 2)) void gemm_nt_kernel(GemmArgs g)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN, ROWS = BM + BN;
     constexpr int SLOTS = 2 * NC;                       // 16-byte pieces per row per stage
     constexpr int A_SLOTS = BM * SLOTS, B_SLOTS = BN * SLOTS;
     constexpr int LA = A_SLOTS / kThreads, LB = B_SLOTS / kThreads, LS = PS ? 0 : ROWS * NC / kThreads;
-    constexpr int NLOAD = LA + LB + (PS ? 1 : LS);       // direct-to-LDS loads per thread per stage
+    constexpr int LG = OUTER ? (ROWS / 64 + 3) / 4 : 0;  // outer-scale copies per thread per stage (64 rows each)
+    constexpr int NSTAGE = LA + LB + LG + (PS ? 0 : LS); // copies per thread that issue_loads() makes for one stage
+    constexpr int NLOAD = NSTAGE + (PS ? 1 : 0);         // direct-to-LDS loads per thread per stage
     constexpr int CODE_BYTES = (A_SLOTS + B_SLOTS) * 16; // one stage of codes; three of them, then the scales
     constexpr int SC_BYTES = PS ? ROWS * 16 : ROWS * NC * 4;   // one scale buffer (a pair of stages / one stage)
     constexpr int SC_BASE = 3 * CODE_BYTES;
+    constexpr int GS_BASE = SC_BASE + 3 * SC_BYTES;      // OUTER: ring of four [ROWS] float buffers
+    static_assert(!OUTER || NC == 2, "a stage must be one 128-k outer block");
+    static_assert(!OUTER || TM * TN <= 8, "two accumulator sets must fit the register file");
     constexpr int STEPS = NC * 4;
     // bf16 output: the MFMA takes the B fragment as its row operand, so that a lane ends up with runs of four
     // consecutive output columns (8-byte stores); FP32 output keeps lanes along the columns (128 contiguous bytes
@@ -207,6 +226,11 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+    float16_t part[OUTER ? TM : 1][OUTER ? TN : 1];      // OUTER: the running sum of the current 128-k block
+    float16_t zero16;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) zero16[e] = 0.0f;
+
     if (nchunks > 0) {
         // Per-lane constants of the loads: 32-bit byte offsets from the tile's (uniform) base pointers, the
         // piece / chunk index each load covers, and a bit mask of the loads whose row exists.
@@ -240,9 +264,34 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
                 soff[h] = ok ? (uint32_t)(isA ? row : row - BM) * (uint32_t)sstride : 0u;
             }
         }
+        // OUTER: copy u of a stage brings the outer scales of rows (q % (ROWS/64)) * 64 .. + 63, q = 4 u + wave (when
+        // ROWS/64 is no multiple of four the surplus copies repeat a block: same values to the same place)
+        uint32_t goff[OUTER ? LG : 1];
+        const int64_t nkb = g.K >> 7;
+        if (OUTER) {
+#pragma unroll
+            for (int u = 0; u < LG; ++u) {
+                const int row = ((u * 4 + wave) % (ROWS / 64)) * 64 + lane;
+                const bool isA = row < BM;
+                const bool ok = (isA ? m0 + row : n0 + row - BM) < (isA ? g.M : g.N);
+                goff[u] = ok ? (uint32_t)(isA ? row : row - BM) * (uint32_t)nkb * 4u : 0u;
+            }
+        }
         const bool tile_full = m0 + BM <= g.M && n0 + BN <= g.N;
         const uint8_t *a_cbase = g.a_codes + m0 * cstride + cbeg * 32, *b_cbase = g.b_codes + n0 * cstride + cbeg * 32;
         const uint8_t *a_sbase = g.a_scales + m0 * sstride + cbeg * 4, *b_sbase = g.b_scales + n0 * sstride + cbeg * 4;
+        // OUTER: outer scales of the tile's rows for the split's first 128-k block (a split starts on a block boundary)
+        const float *a_gbase = OUTER ? g.a_gscale + m0 * nkb + (cbeg >> 1) : nullptr;
+        const float *b_gbase = OUTER ? g.b_gscale + n0 * nkb + (cbeg >> 1) : nullptr;
+        auto issue_outer = [&](int kt) {
+            // stage kt = block kt of the split, into ring slot kt % 4; stages past the end re-fetch block 0 (never used)
+            const int kb = (int64_t)kt * NC < nchunks ? kt : 0;
+#pragma unroll
+            for (int u = 0; u < LG; ++u) {
+                const int rb = (u * 4 + wave) % (ROWS / 64);
+                lds_dma4(to_scalar((rb * 64 < BM ? a_gbase : b_gbase) + kb), goff[u], lds_base + GS_BASE + ((kt & 3) * ROWS + rb * 64) * 4);
+            }
+        };
 
         // All loads of stage kt.  Interior tiles and stages fully inside the split take the straight path;
         // otherwise loads of missing rows or of chunks past the end are skipped (their LDS slots keep stale
@@ -286,6 +335,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
                              sdst + q * 256);
                 }
             }
+            if (OUTER) issue_outer(kt);
         };
         // PS: half h of scale pair P (16 scale bytes = 256 k per row) into pair buffer P % 3; pairs past the end
         // re-fetch pair 0 (valid memory, never consumed)
@@ -355,7 +405,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
             issue_scale_half(0, 0); issue_scale_half(0, 1);
             issue_scale_half(1, 0); issue_scale_half(1, 1);
             issue_loads(1, 1);
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (LA + LB));   // everything but stage 1's codes has landed
+            __builtin_amdgcn_s_waitcnt(0x0F70 | NSTAGE);      // everything but stage 1's own copies has landed
         } else {
             issue_loads(1, 1);
             __builtin_amdgcn_s_waitcnt(0x0F70 | NLOAD);       // vmcnt(NLOAD): stage 0 has landed
@@ -385,9 +435,12 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].b[j], op[gs & 1].a[i], acc[i][j], 0, 0, 0)
-                                         : __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].a[i], op[gs & 1].b[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < TN; ++j) {
+                        float16_t &dst = OUTER ? part[i][j] : acc[i][j];
+                        const float16_t addend = (OUTER && gs == 0) ? zero16 : dst;
+                        dst = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].b[j], op[gs & 1].a[i], addend, 0, 0, 0)
+                                   : __builtin_amdgcn_mfma_f32_32x32x16_f16(op[gs & 1].a[i], op[gs & 1].b[j], addend, 0, 0, 0);
+                    }
                 // issue order: one MFMA, then (in the steps that fetch raw fragments) two LDS reads, then its
                 // share of the expansion's VALU instructions
                 const bool fetch = (ks == 1 && c + 1 < NC) || gs == STEPS - 2;
@@ -401,20 +454,54 @@ __global__ __launch_bounds__(kThreads, (TM * TN >= 8 ? 1 : 2)) void gemm_nt_kern
                     __builtin_amdgcn_sched_group_barrier(0x002, (8 * (TM + TN) + TM * TN - 1) / (TM * TN) + 1, 0);
                 }
             }
+            if (OUTER) {
+                // end of the stage = end of outer block kt: total += stage_sum * S_A[m] * S_B[n].  The block's scales
+                // landed before the previous stage's barrier; ring slot kt % 4 is next written by the copies of stage
+                // kt + 4, which are issued after the NEXT stage's barrier, so every wave is done reading by then.
+                // The side that varies with the accumulator element (columns when SWAP, rows otherwise) is read as four
+                // runs of four consecutive floats, the other side is one float per lane and tile.
+                const float *gsr = reinterpret_cast<const float *>(smem_raw + GS_BASE) + (kt & 3) * ROWS;
+                float s_lane[SWAP ? TM : TN];
+                if (SWAP) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) s_lane[i] = gsr[(wm * TM + i) * 32 + lr];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) s_lane[j] = gsr[BM + (wn * TN + j) * 32 + lr];
+                }
+#pragma unroll
+                for (int v = 0; v < (SWAP ? TN : TM); ++v) {
+                    const float *base = SWAP ? gsr + BM + (wn * TN + v) * 32 + 4 * kg : gsr + (wm * TM + v) * 32 + 4 * kg;
+                    float4 sv[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) sv[q] = *reinterpret_cast<const float4 *>(base + 8 * q);
+#pragma unroll
+                    for (int w = 0; w < (SWAP ? TM : TN); ++w) {
+                        const int i = SWAP ? w : v, j = SWAP ? v : w;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            acc[i][j][4 * q + 0] = __builtin_fmaf(part[i][j][4 * q + 0], sv[q].x * s_lane[w], acc[i][j][4 * q + 0]);
+                            acc[i][j][4 * q + 1] = __builtin_fmaf(part[i][j][4 * q + 1], sv[q].y * s_lane[w], acc[i][j][4 * q + 1]);
+                            acc[i][j][4 * q + 2] = __builtin_fmaf(part[i][j][4 * q + 2], sv[q].z * s_lane[w], acc[i][j][4 * q + 2]);
+                            acc[i][j][4 * q + 3] = __builtin_fmaf(part[i][j][4 * q + 3], sv[q].w * s_lane[w], acc[i][j][4 * q + 3]);
+                        }
+                    }
+                }
+            }
             buf = nbuf;
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the look-ahead loads before the LDS is released
     }
 
-    store_tile<TM, TN, OUT, SWAP>(acc, g, m0, n0, wm, wn, lr, kg);
+    store_tile<TM, TN, OUT, SWAP, OUTER>(acc, g, m0, n0, wm, wn, lr, kg);
 }
 
-template <int TM, int TN, int OUT, bool PS>
+template <int TM, int TN, int OUT, bool PS, int OUTER>
 hipError_t launch_cfg(const GemmArgs &g, dim3 grid, hipStream_t st)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int lds = 3 * ((BM + BN) * 2 * kNC * 16 + (BM + BN) * (PS ? 16 : kNC * 4));
-    auto kern = gemm_nt_kernel<TM, TN, kNC, OUT, PS>;
+    constexpr int lds = 3 * ((BM + BN) * 2 * kNC * 16 + (BM + BN) * (PS ? 16 : kNC * 4)) + (OUTER ? 4 * (BM + BN) * 4 : 0);
+    auto kern = gemm_nt_kernel<TM, TN, kNC, OUT, PS, OUTER>;
     // once per instantiation; the initialisation of a function-local static is thread-safe
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -423,17 +510,21 @@ hipError_t launch_cfg(const GemmArgs &g, dim3 grid, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int OUT, bool PS>
+// tile: 0 256x256 (tensor mode only: block mode needs two accumulator sets), 1 256x128, 2 128x256, 3 128x128,
+// 4 128x192 (paired scale fetch only)
+template <int OUT, bool PS, int OUTER>
 hipError_t launch_tile(int tile, const GemmArgs &g, dim3 grid, hipStream_t st)
 {
     switch (tile) {
-        case 0: return launch_cfg<4, 4, OUT, PS>(g, grid, st);
-        case 1: return launch_cfg<4, 2, OUT, PS>(g, grid, st);
-        case 2: return launch_cfg<2, 4, OUT, PS>(g, grid, st);
-        case 4:
-            if constexpr (PS) return launch_cfg<2, 3, OUT, true>(g, grid, st);
+        case 0:
+            if constexpr (OUTER == 0) return launch_cfg<4, 4, OUT, PS, 0>(g, grid, st);
             else return hipErrorInvalidValue;
-        default: return launch_cfg<2, 2, OUT, PS>(g, grid, st);
+        case 1: return launch_cfg<4, 2, OUT, PS, OUTER>(g, grid, st);
+        case 2: return launch_cfg<2, 4, OUT, PS, OUTER>(g, grid, st);
+        case 4:
+            if constexpr (PS) return launch_cfg<2, 3, OUT, true, OUTER>(g, grid, st);
+            else return hipErrorInvalidValue;
+        default: return launch_cfg<2, 2, OUT, PS, OUTER>(g, grid, st);
     }
 }
 

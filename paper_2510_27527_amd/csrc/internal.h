@@ -72,14 +72,15 @@ hipError_t launch_requant_col_pair(const PackedSrc &src0, int64_t R0, int64_t C0
 struct GemmOperand {
     const uint8_t *codes;
     const uint8_t *scales;
-    const float *gscale;   // tensor-mode scalar
+    const float *gscale;   // one float, or [rows][K/128] floats
     int64_t rows;
+    int outer;             // 0 tensor mode, 1 one outer scale per row and 128 k (both operands alike)
 };
 
 // Out[M x N] = A[M x K] * B[N x K]^T; splitk_ws holds split * M * N floats when split > 1
-size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int outer);
 // workgroup tile and K split the launcher will use for this shape
-void gemm_plan(int64_t M, int64_t N, int64_t K, int *bm, int *bn, int *split);
+void gemm_plan(int64_t M, int64_t N, int64_t K, int outer, int *bm, int *bn, int *split);
 hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K, void *out, int out_f32,
                           void *ws, size_t ws_bytes, hipStream_t st);
 

@@ -3,10 +3,9 @@
 //   amax_partials   per-tensor max|x| of a bf16 array (TENSOR outer mode only)
 //   quant_row       groups of 16 along the contiguous axis; 8 elements (one 128-bit load) per
 //                   lane, two lanes per group, group maximum exchanged by DPP
-//   quant_col       groups of 16 down the columns: a 128 x 64 tile goes through LDS (rotated so
-//                   both the 128-bit row writes and the per-column reads are conflict free), each
-//                   lane then owns two columns x 16 rows; the output is the transposed operand
-//   requant_col     same, the source being a packed NVFP4 tensor (Q4 / Q6)
+//   quant_colw      groups of 16 down the columns, bf16 or packed NVFP4 source (Q5; Q4 / Q6): a wave owns a
+//                   128 x 128 strip, a lane two columns; the output is the transposed operand
+//   quant_dual      row-wise and column-wise operand of one bf16 tensor from one read (Q3 + Q5)
 #include <type_traits>
 
 #include "device_fmt.h"
@@ -266,6 +265,7 @@ struct ColArgs {
     const uint8_t *src_codes;  // packed source
     const uint8_t *src_scales;
     const float *src_gscale;
+    int src_outer;             // packed source: 0 one scale for the tensor, 1 one per row and 128 columns
     int64_t R, C;
     int span;                  // consecutive row tiles (of one column tile) per workgroup
     KArgs k;
@@ -275,65 +275,25 @@ struct ColArgs {
 // dword column of the tile, rotated by 4 per 16 rows
 __device__ __forceinline__ int tile_pos(int row, int dwcol) { return row * 32 + ((dwcol + 4 * (row >> 4)) & 31); }
 
-// 16 packed codes of one source group times its scale, as 8 dwords of bf16 pairs (exact: 6 significant bits).
-// The hardware conversion turns a byte into two binary32 values (signed zeros included); the product with the scale
-// is exact, and its upper half is the bf16 value.
-__device__ __forceinline__ void decode_group_bf16(uint2 codes, uint32_t sc, uint32_t (&out)[8])
-{
-    const float sb = e4m3_value(sc);
-    const float2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 0) * sb;
-    const float2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 1) * sb;
-    const float2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 2) * sb;
-    const float2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.x, 1.0f, 3) * sb;
-    const float2_t p4 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 0) * sb;
-    const float2_t p5 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 1) * sb;
-    const float2_t p6 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 2) * sb;
-    const float2_t p7 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes.y, 1.0f, 3) * sb;
-    const float2_t p[8] = {p0, p1, p2, p3, p4, p5, p6, p7};
-#pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = __builtin_amdgcn_perm(f2u(p[i].y), f2u(p[i].x), 0x07060302u);
-}
-
-// what one thread brings in for one tile
-template <bool PACKED>
-struct ColFetch {
-    uint4 v[4];                // bf16: 8 elements of rows (tid >> 3) + 32 * pass
-};
-template <>
-struct ColFetch<true> {
-    uint2 cw[2];               // packed: two groups of 16 codes of row tid >> 1 ...
-    uint32_t sc[2];            // ... and their scale bytes
-};
-
-// A workgroup takes `span` consecutive row tiles of one column tile (blockIdx.x = column tile, blockIdx.y = run of
-// row tiles): the scale set-up is paid once, the next tile's loads are in flight while the current one is quantized,
-// and the halves of an output line (128 source rows give 64 bytes of codes per column) are written close in time.
-// DUAL (bf16 source only): the tile's rows are also quantized row-wise (groups along C) while they pass through
-// registers on the way into LDS, so one read of the source yields both backward operands of dY (Q3 and Q5).
-template <int ROUND, bool SUP, bool PACKED, bool DUAL = false>
-__global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs a1, unsigned first_second)
+// Row-wise AND column-wise operand of one bf16 tensor from a single read of it (Q3 and Q5 of dY).  A workgroup takes
+// `span` consecutive 128 x 64 tiles down one column of tiles (blockIdx.x = column tile fastest): the scale set-up is
+// paid once and the next tile's loads are in flight while the current one is quantized.  Each tile goes through LDS
+// as bf16 pairs (rotated so that the 128-bit row writes and the per-column reads are both conflict free); on the way in,
+// while a row passes through registers, it is quantized row-wise (groups along C); after the transpose a lane owns
+// two columns x 16 rows = two groups of the column-wise operand.
+template <int ROUND, bool SUP>
+__global__ __launch_bounds__(kThreads) void quant_dual_kernel(ColArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint32_t tile[kTileR * 32];
     __shared__ float inv_tab[128];
     __shared__ float red[4];
     __shared__ float os_sh[4];
     const int tid = threadIdx.x;
-    // one launch can serve two tensors: workgroups from first_second on take the second job
-    const bool second = blockIdx.x >= first_second;
-    const ColArgs a = second ? a1 : a0;
-    const uint32_t lin0 = second ? blockIdx.x - first_second : blockIdx.x;
+    const uint32_t lin0 = blockIdx.x;
     const int64_t R = a.R, C = a.C;
     const uint32_t tiles_r = (uint32_t)((R + kTileR - 1) / kTileR);
     const uint32_t gx = (uint32_t)((C + kTileC - 1) / kTileC);              // column tiles
-    const uint32_t gy = (tiles_r + (uint32_t)a.span - 1) / (uint32_t)a.span; // runs of row tiles
-    uint32_t lin = lin0;
-    if (PACKED) {
-        // Workgroup ids are dealt round-robin over the 8 XCDs.  A packed source has only 32 bytes of codes per row and
-        // tile, so there each XCD gets a contiguous run of workgroups (column tile fastest): neighbouring column
-        // tiles, which share the source's cache lines, then meet in one L2.
-        const uint32_t per_xcd = gx * gy / 8;
-        if (lin < per_xcd * 8) lin = (lin & 7) * per_xcd + (lin >> 3);
-    }
+    const uint32_t lin = lin0;
     // workgroup-uniform: keep them (and everything derived from them) in scalar registers
     const uint32_t by = __builtin_amdgcn_readfirstlane(lin / gx), bx = __builtin_amdgcn_readfirstlane(lin % gx);
     const int64_t C0 = (int64_t)bx * kTileC;
@@ -341,35 +301,21 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
     const int ntile = (int)min((uint32_t)a.span, tiles_r - rt0);
 
     // ---- loads of one tile into registers (nothing here depends on the scale set-up)
-    const int64_t ld_row = PACKED ? (tid >> 1) : (tid >> 3);
-    const int64_t ld_col = C0 + (PACKED ? 32 * (tid & 1) : 8 * (tid & 7));
+    const int64_t ld_row = tid >> 3;
+    const int64_t ld_col = C0 + 8 * (tid & 7);
     // element index of the thread's first load: its own part once, the tile's (workgroup-uniform) part per tile
     const int64_t ld_lane = ld_row * C + ld_col;
-    auto fetch = [&](int t, ColFetch<PACKED> &f) {
+    struct Fetch { uint4 v[4]; };                                            // 8 elements of rows (tid >> 3) + 32 * pass
+    auto fetch = [&](int t, Fetch &f) {
         const int64_t R0 = (int64_t)(rt0 + t) * kTileR;
-        if constexpr (!PACKED) {
 #pragma unroll
-            for (int pass = 0; pass < 4; ++pass) {
-                const int64_t r_uni = R0 + pass * 32;                       // uniform
-                f.v[pass] = make_uint4(0, 0, 0, 0);
-                if (r_uni + ld_row < R && ld_col < C) f.v[pass] = ld_stream(a.src + ((r_uni * C + ld_lane) >> 3));
-            }
-        } else {
-            const int64_t e_uni = R0 * C;                                   // uniform
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const int64_t gc = ld_col + 16 * b;
-                f.cw[b] = make_uint2(0, 0);
-                f.sc[b] = 0;
-                if (R0 + ld_row < R && gc < C) {
-                    const int64_t e = e_uni + ld_lane + 16 * b;
-                    f.cw[b] = *reinterpret_cast<const uint2 *>(a.src_codes + (e >> 1));
-                    f.sc[b] = a.src_scales[e >> 4];
-                }
-            }
+        for (int pass = 0; pass < 4; ++pass) {
+            const int64_t r_uni = R0 + pass * 32;                           // uniform
+            f.v[pass] = make_uint4(0, 0, 0, 0);
+            if (r_uni + ld_row < R && ld_col < C) f.v[pass] = ld_stream(a.src + ((r_uni * C + ld_lane) >> 3));
         }
     };
-    ColFetch<PACKED> cur;
+    Fetch cur;
     fetch(0, cur);
 
     // ---- set-up, once per workgroup: reciprocal table (waves 0, 1), outer scale (wave 2)
@@ -383,11 +329,10 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
             os_sh[2] = o.inv_cg;
             if (lin0 == 0) {
                 a.k.gscale[0] = o.S_g;
-                if (DUAL) a.krow.gscale[0] = o.S_g;
+                a.krow.gscale[0] = o.S_g;
             }
         }
     }
-    const float src_sg = PACKED ? a.src_gscale[0] : 1.0f;
     __syncthreads();
     OuterScale os;
     os.S_g = os_sh[0];
@@ -403,47 +348,35 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
         const int64_t R0 = (int64_t)(rt0 + t) * kTileR;
         if (t > 0) __syncthreads();                         // everyone is done reading the previous tile
         // phase 1: tile -> LDS as bf16 pairs, row-major with rotated columns
-        if constexpr (!PACKED) {
 #pragma unroll
-            for (int pass = 0; pass < 4; ++pass) {
-                const int row = pass * 32 + (tid >> 3), q = tid & 7;
-                const uint4 v = cur.v[pass];
-                *reinterpret_cast<uint4 *>(&tile[tile_pos(row, q * 4)]) = v;
-                if (DUAL) {
-                    // row-wise: lanes q, q^1 hold one group of 16 along C
-                    const int64_t gr = R0 + row;
-                    const bool valid = gr < R && ld_col < C;
-                    const uint32_t hm = absmax8_bits(v);
-                    const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
-                    const uint32_t bm = hm > o1 ? hm : o1;
-                    const uint32_t sc = e4m3_round<SUP>(u2f(bm << 16) * os.inv_cg);
-                    const float r = os.inv_sg * inv_tab[sc];
-                    const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
-                                        bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-                    const int64_t e0 = (R0 + pass * 32) * C + ld_lane;
-                    const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 2), a.krow.k0, a.krow.k1);
-                    if (valid) a.krow.codes[e0 >> 3] = qd;
-                    const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
-                    const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
-                    if (valid && q == 0) {
-                        if ((C & 63) == 0) {
-                            *reinterpret_cast<uint32_t *>(a.krow.scales + (e0 >> 4)) = s4;
-                        } else {
-                            for (int b = 0; b < 4; ++b)
-                                if (ld_col + 16 * b < C) a.krow.scales[(e0 >> 4) + b] = (uint8_t)(s4 >> (8 * b));
-                        }
+        for (int pass = 0; pass < 4; ++pass) {
+            const int row = pass * 32 + (tid >> 3), q = tid & 7;
+            const uint4 v = cur.v[pass];
+            *reinterpret_cast<uint4 *>(&tile[tile_pos(row, q * 4)]) = v;
+            {
+                // row-wise: lanes q, q^1 hold one group of 16 along C
+                const int64_t gr = R0 + row;
+                const bool valid = gr < R && ld_col < C;
+                const uint32_t hm = absmax8_bits(v);
+                const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
+                const uint32_t bm = hm > o1 ? hm : o1;
+                const uint32_t sc = e4m3_round<SUP>(u2f(bm << 16) * os.inv_cg);
+                const float r = os.inv_sg * inv_tab[sc];
+                const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                                    bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+                const int64_t e0 = (R0 + pass * 32) * C + ld_lane;
+                const uint32_t qd = quant8<ROUND, SUP>(x, r, (uint32_t)(e0 >> 2), a.krow.k0, a.krow.k1);
+                if (valid) a.krow.codes[e0 >> 3] = qd;
+                const uint32_t s2 = sc | (dpp<DPP_ROW_SHL2>(sc) << 8);
+                const uint32_t s4 = s2 | (dpp<DPP_ROW_SHL4>(s2) << 16);
+                if (valid && q == 0) {
+                    if ((C & 63) == 0) {
+                        *reinterpret_cast<uint32_t *>(a.krow.scales + (e0 >> 4)) = s4;
+                    } else {
+                        for (int b = 0; b < 4; ++b)
+                            if (ld_col + 16 * b < C) a.krow.scales[(e0 >> 4) + b] = (uint8_t)(s4 >> (8 * b));
                     }
                 }
-            }
-        } else {
-            const int row = tid >> 1, half = tid & 1;
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                uint32_t d[8];
-                decode_group_bf16(cur.cw[b], cur.sc[b], d);
-                const int dw = 16 * half + 8 * b;
-                *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw)]) = make_uint4(d[0], d[1], d[2], d[3]);
-                *reinterpret_cast<uint4 *>(&tile[tile_pos(row, dw + 4)]) = make_uint4(d[4], d[5], d[6], d[7]);
             }
         }
         __syncthreads();
@@ -466,10 +399,8 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
             for (int i = 0; i < 8; ++i) {
                 x0[i] = j == 0 ? bf16_lo(w[i]) : bf16_hi(w[i]);
                 x1[i] = j == 0 ? bf16_lo(w[8 + i]) : bf16_hi(w[8 + i]);
-                if (PACKED) { x0[i] = x0[i] * src_sg; x1[i] = x1[i] * src_sg; }
             }
             float m = u2f((uint32_t)(j == 0 ? m2.x : m2.y) << 16);
-            if (PACKED) m = m * src_sg;                                     // rounding is monotone: = max |x|
             const float s = m * os.inv_cg;
             const uint32_t sc = e4m3_round<SUP>(s);
             const float r = os.inv_sg * inv_tab[sc];
@@ -482,6 +413,244 @@ __global__ __launch_bounds__(kThreads) void quant_col_kernel(ColArgs a0, ColArgs
             a.k.scales[e >> 4] = (uint8_t)sc;
         }
     }
+}
+
+
+// ------------------------------------------------------------- column-wise, one strip per wave ----
+//
+// Groups of 16 run down the columns of the source [R x C]; the output is the transposed operand [C x R].  A wave
+// owns a strip of 128 source columns x 128 source rows (8 slabs of 16 rows): lane l holds columns 2 l, 2 l + 1 of a
+// slab as 16 registers (one dword of two bf16 per row - a wave load is 256 contiguous bytes of a row; or one byte of
+// two codes per row for a packed source), i.e. two complete groups, with no exchange between lanes and no barrier
+// while it quantizes.  The four waves of a workgroup take four strips below each other, so for each of the 128
+// output rows the workgroup produces 256 contiguous bytes of codes and 32 of scales; these are gathered in LDS and
+// written after the workgroup's only barrier, whole runs per store instruction (measured on this chip: 16-byte
+// pieces scattered over rows 2.3 TB/s, 64-byte runs 4.2, 256-byte runs 4.6; 8-byte scale pieces cost as much as all
+// the codes).  With a 1 x 128 outer block (OUTER = 1) a strip's 128 rows are exactly one outer block of each of its
+// output rows: a first pass over the strip takes the column maxima, the second pass (the same addresses again, now
+// from cache) quantizes.
+constexpr int kStripC = 128, kStripR = 128, kSlabs = kStripR / 16;
+
+template <int ROUND, bool SUP, bool PACKED, int OUTER>
+__global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArgs a1, unsigned first_second)
+{
+    __shared__ float inv_tab[128];
+    __shared__ float red[4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const bool second = blockIdx.x >= first_second;
+    const ColArgs a = second ? a1 : a0;
+    const uint32_t wg0 = second ? blockIdx.x - first_second : blockIdx.x;
+    // Workgroup ids are dealt round-robin over the 8 XCDs.  Each XCD gets a contiguous run of this job's strips (column
+    // index fastest, so whole bands of strip rows): its strips then cover every column offset - all of the cache's
+    // channels, where a strided walk down one column offset would keep hitting the same few - and neighbouring strips,
+    // which share cache lines of a packed source, meet in one L2.  Measured on 8192 x 8192 bf16: 6.1 TB/s against 4.0.
+    uint32_t wg = wg0;
+    {
+        const uint32_t nwg = second ? gridDim.x - first_second : (first_second < gridDim.x ? first_second : gridDim.x);
+        const uint32_t per_xcd = nwg / 8;
+        if (wg < per_xcd * 8) wg = (wg & 7) * per_xcd + (wg >> 3);
+    }
+    fill_inv_table(inv_tab);
+    OuterScale os[2];
+    if (OUTER == 0) {
+        os[0] = os[1] = outer_scale(block_tensor_amax(a.k, red));
+        if (wg0 == 0 && tid == 0) a.k.gscale[0] = os[0].S_g;
+    }
+    __syncthreads();
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t R = a.R, C = a.C;
+    constexpr int kWaves = kThreads / 64;
+    const uint32_t tiles_c = (uint32_t)((C + kStripC - 1) / kStripC), tiles_r = (uint32_t)((R + kStripR - 1) / kStripR);
+    // wave-uniform: keep them (and every address derived from them) in scalar registers
+    const uint32_t tc = __builtin_amdgcn_readfirstlane(wg % tiles_c), trg = __builtin_amdgcn_readfirstlane(wg / tiles_c);
+    const uint32_t tr = trg * kWaves + wave;
+    const bool have = tr < tiles_r;                                // this wave has a strip (all of them reach the barrier)
+    // strips of this workgroup that are whole and whose output runs are 16-byte aligned: these go out through LDS
+    const int nwide = (R & 127) == 0 ? (int)min((uint32_t)kWaves, tiles_r - trg * kWaves) : 0;
+    const int64_t R0 = (int64_t)tr * kStripR, c0 = (int64_t)tc * kStripC + 2 * lane;
+    const bool colok = c0 < C;                                     // C is even: both columns or none
+    const int nslab = have ? (int)min((int64_t)kSlabs, (R - R0) >> 4) : 0;    // R is a multiple of 16
+
+    // One slab = 16 rows x the lane's two columns.  Every address is a wave-uniform row pointer plus a 32-bit lane
+    // index, so the loads need no per-lane address arithmetic and no predication: lanes past the last column read
+    // column pair 0 of the strip (valid memory) and are never stored.  fetch() only issues the loads (raw words stay
+    // in registers); decode() turns them into binary32, x0[i], x1[i] = source(R0 + 16 s + i, c0), (.., c0 + 1).
+    // The next slab is fetched before the current one is decoded, so a wave always has a slab in flight.
+    const uint32_t ln = colok ? (uint32_t)lane : 0u;
+    const int64_t strip0 = (int64_t)tc * kStripC;                  // first column of the strip (uniform)
+    const float src_sg_tensor = (PACKED && a.src_outer == 0) ? a.src_gscale[0] : 1.0f;
+    struct Raw {
+        uint32_t w[16];                                            // bf16 pairs, or bytes of two codes
+        uint32_t sb[PACKED ? 16 : 1];                              // packed: scale bytes
+    };
+    // packed source with 1 x 128 outer blocks: the strip lies inside one block column, so each of its 128 rows has one
+    // outer scale; the wave keeps them in its own corner of LDS
+    __shared__ float row_sg_all[PACKED ? kThreads / 64 : 1][PACKED ? kStripR : 1];
+    float *row_sg = row_sg_all[PACKED ? wave : 0];
+    const bool src_blocks = PACKED && a.src_outer != 0;
+    if (src_blocks && have) {
+        const int64_t nbc = C >> 7;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int64_t row = R0 + lane + 64 * h;
+            row_sg[lane + 64 * h] = row < R ? a.src_gscale[row * nbc + tc] : 0.0f;
+        }
+        // same wave writes and reads: the compiler's wait on the LDS counter orders them
+    }
+    auto fetch = [&](auto stream, int s, Raw &r) {
+        constexpr bool STREAM = decltype(stream)::value;          // last use of these bytes: they need not stay cached
+        const int64_t e0 = (R0 + 16 * s) * C + strip0;             // uniform
+        if constexpr (!PACKED) {
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(a.src) + (e0 >> 1);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t *rowp = p + i * (C >> 1);           // uniform
+                r.w[i] = STREAM ? __builtin_nontemporal_load(rowp + ln) : rowp[ln];
+            }
+        } else {
+            const uint8_t *pc = a.src_codes + (e0 >> 1);
+            const uint8_t *ps = a.src_scales + (e0 >> 4);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                r.w[i] = (pc + i * (C >> 1))[ln];
+                r.sb[i] = (ps + i * (C >> 4))[ln >> 3];
+            }
+        }
+    };
+    // returns the two column maxima of the slab
+    auto decode = [&](const Raw &r, int s, float (&x0)[16], float (&x1)[16], float &m0, float &m1) {
+        if constexpr (!PACKED) {
+            ushort2_t m2 = {0, 0};
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                m2 = __builtin_elementwise_max(m2, as_us2(r.w[i] & 0x7FFF7FFFu));
+                x0[i] = bf16_lo(r.w[i]);
+                x1[i] = bf16_hi(r.w[i]);
+            }
+            m0 = u2f((uint32_t)m2.x << 16);
+            m1 = u2f((uint32_t)m2.y << 16);
+        } else {
+            m0 = m1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float sg = src_blocks ? row_sg[16 * s + i] : src_sg_tensor;
+                const float2_t pv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r.w[i], 1.0f, 0) * e4m3_value(r.sb[i]);   // exact
+                x0[i] = pv.x * sg;                                  // the binary32 dequantized value: one rounding
+                x1[i] = pv.y * sg;
+                m0 = fmaxf(m0, fabsf(x0[i]));
+                m1 = fmaxf(m1, fabsf(x1[i]));
+            }
+        }
+    };
+
+    Raw cur, nxt;
+    if (OUTER == 1 && have) {
+        // first pass: the maximum of each column over the strip's 128 rows = one outer block of the output row
+        float cm0 = 0.0f, cm1 = 0.0f;
+        fetch(std::false_type{}, 0, cur);
+#pragma unroll
+        for (int s = 0; s < kSlabs; ++s) {
+            if (s >= nslab) break;
+            if (s + 1 < nslab) fetch(std::false_type{}, s + 1, nxt);
+            if constexpr (!PACKED) {
+                ushort2_t m2 = {0, 0};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) m2 = __builtin_elementwise_max(m2, as_us2(cur.w[i] & 0x7FFF7FFFu));
+                cm0 = fmaxf(cm0, u2f((uint32_t)m2.x << 16));
+                cm1 = fmaxf(cm1, u2f((uint32_t)m2.y << 16));
+            } else {
+                float x0[16], x1[16], m0, m1;
+                decode(cur, s, x0, x1, m0, m1);
+                cm0 = fmaxf(cm0, m0);
+                cm1 = fmaxf(cm1, m1);
+            }
+            cur = nxt;
+        }
+        os[0] = outer_scale(cm0);
+        os[1] = outer_scale(cm1);
+        if (colok) {
+            const int64_t nb = R >> 7;
+            a.k.gscale[c0 * nb + tr] = os[0].S_g;
+            a.k.gscale[(c0 + 1) * nb + tr] = os[1].S_g;
+        }
+    }
+
+    // Codes and scale bytes of the workgroup's whole strips are gathered in LDS: [output row][wave][64 + 8 bytes].
+    // Code row pitch 264 bytes (256 + 8) spreads the lanes' 8-byte writes over the banks.
+    constexpr int kPitch = kWaves * 64 + 8, kScPitch = kWaves * 8;
+    __shared__ __attribute__((aligned(16))) uint8_t stage[kStripC * kPitch];
+    __shared__ __attribute__((aligned(16))) uint8_t sc_stage[kStripC * kScPitch];
+    uint32_t scb[2][2] = {{0, 0}, {0, 0}};                          // scale bytes of slabs 0..3 and 4..7, per column
+    const bool wide = (int)wave < nwide;
+    if (have) fetch(std::true_type{}, 0, cur);
+#pragma unroll
+    for (int s = 0; s < kSlabs; ++s) {
+        if (s >= nslab) break;
+        if (s + 1 < nslab) fetch(std::true_type{}, s + 1, nxt);
+        float x0[16], x1[16], mx[2];
+        decode(cur, s, x0, x1, mx[0], mx[1]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const float (&x)[16] = j == 0 ? x0 : x1;
+            const uint32_t sc = e4m3_round<SUP>(mx[j] * os[j].inv_cg);
+            const float r = os[j].inv_sg * inv_tab[sc];
+            const int64_t e = (c0 + j) * R + R0 + 16 * s;           // index in the output's [C x R] view
+            const uint32_t quad0 = (uint32_t)(e >> 2);
+            const float xa[8] = {x[0], x[1], x[2], x[3], x[4], x[5], x[6], x[7]};
+            const float xb[8] = {x[8], x[9], x[10], x[11], x[12], x[13], x[14], x[15]};
+            uint2 q;
+            q.x = quant8<ROUND, SUP>(xa, r, quad0, a.k.k0, a.k.k1);
+            q.y = quant8<ROUND, SUP>(xb, r, quad0 + 2, a.k.k0, a.k.k1);
+            scb[j][s >> 2] |= sc << (8 * (s & 3));
+            if (wide) {
+                *reinterpret_cast<uint2 *>(stage + (2 * lane + j) * kPitch + wave * 64 + 8 * s) = q;
+            } else if (colok) {
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(a.k.codes) + (e >> 1)) = q;
+                a.k.scales[e >> 4] = (uint8_t)sc;
+            }
+        }
+        cur = nxt;
+    }
+    if (nwide == 0) return;                                         // uniform over the workgroup
+    if (wide) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            *reinterpret_cast<uint2 *>(sc_stage + (2 * lane + j) * kScPitch + wave * 8) = make_uint2(scb[j][0], scb[j][1]);
+    }
+    __syncthreads();
+    {
+        // codes: 16 lanes x 16 bytes cover one output row's 256-byte run; 16 rows per pass
+        const int64_t Rg = (int64_t)trg * kWaves * kStripR;        // first source row of the workgroup
+        const int piece = tid & 15;
+        uint8_t *out_codes = reinterpret_cast<uint8_t *>(a.k.codes);
+        if (piece < 4 * nwide) {
+#pragma unroll
+            for (int it = 0; it < kStripC / 16; ++it) {
+                const int row = it * 16 + (tid >> 4);
+                const uint2 lo = *reinterpret_cast<const uint2 *>(stage + row * kPitch + piece * 16);
+                const uint2 hi = *reinterpret_cast<const uint2 *>(stage + row * kPitch + piece * 16 + 8);
+                const int64_t c = strip0 + row;
+                if (c < C) *reinterpret_cast<uint4 *>(out_codes + ((c * R + Rg) >> 1) + piece * 16) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+        }
+        // scales: 4 lanes x 8 bytes cover one output row's 32-byte run; 64 rows per pass
+        const int sp = tid & 3;
+        if (sp < nwide) {
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int row = it * 64 + (tid >> 2);
+                const uint2 v = *reinterpret_cast<const uint2 *>(sc_stage + row * kScPitch + sp * 8);
+                const int64_t c = strip0 + row;
+                if (c < C) *reinterpret_cast<uint2 *>(a.k.scales + ((c * R + Rg) >> 4) + sp * 8) = v;
+            }
+        }
+    }
+}
+
+inline unsigned colw_grid(const ColArgs &a)
+{
+    const int64_t tiles_c = (a.C + kStripC - 1) / kStripC, tiles_r = (a.R + kStripR - 1) / kStripR;
+    return (unsigned)(tiles_c * ((tiles_r + kThreads / 64 - 1) / (kThreads / 64)));
 }
 
 // number of workgroups of a column job (and its span): a workgroup takes several tiles only when there are more than
@@ -524,19 +693,26 @@ void launch_row_t(const RowJob &j0, const RowJob &j1, bool deq, hipStream_t st)
                            first_second);
 }
 
-template <bool PACKED>
-void launch_col_t(ColArgs &a0, ColArgs &a1, bool pair, int rounding, int scale_up, hipStream_t st)
+template <bool PACKED, int OUTER>
+void launch_colw_t(const ColArgs &a0, const ColArgs &a1, bool pair, int rounding, int scale_up, hipStream_t st)
 {
-    const unsigned g0 = col_grid(a0), g1 = pair ? col_grid(a1) : 0;
+    const unsigned g0 = colw_grid(a0), g1 = pair ? colw_grid(a1) : 0;
     const unsigned first_second = pair ? g0 : 0xFFFFFFFFu;
     const dim3 grid(g0 + g1);
     if (rounding == 0) {
-        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<0, true, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
-        else          hipLaunchKernelGGL((quant_col_kernel<0, false, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        if (scale_up) hipLaunchKernelGGL((quant_colw_kernel<0, true, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        else          hipLaunchKernelGGL((quant_colw_kernel<0, false, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
     } else {
-        if (scale_up) hipLaunchKernelGGL((quant_col_kernel<1, true, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
-        else          hipLaunchKernelGGL((quant_col_kernel<1, false, PACKED>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        if (scale_up) hipLaunchKernelGGL((quant_colw_kernel<1, true, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        else          hipLaunchKernelGGL((quant_colw_kernel<1, false, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
     }
+}
+
+template <bool PACKED>
+void launch_colw(const ColArgs &a0, const ColArgs &a1, bool pair, const QuantParams &p, hipStream_t st)
+{
+    if (p.outer == 0) launch_colw_t<PACKED, 0>(a0, a1, pair, p.rounding, p.scale_up, st);
+    else launch_colw_t<PACKED, 1>(a0, a1, pair, p.rounding, p.scale_up, st);
 }
 
 }  // namespace
@@ -623,7 +799,7 @@ hipError_t launch_quant_col_bf16(const void *src, int64_t R, int64_t C, const Qu
     a.C = C;
     a.k = make_kargs(p, o);
     ColArgs none{};
-    launch_col_t<false>(a, none, false, p.rounding, p.scale_up, st);
+    launch_colw<false>(a, none, false, p, st);
     return hipGetLastError();
 }
 
@@ -638,14 +814,12 @@ hipError_t launch_quant_dual_bf16(const void *src, int64_t R, int64_t C, const Q
     a.k = make_kargs(pcol, ocol);
     a.krow = make_kargs(prow, orow);
     const dim3 grid(col_grid(a));
-    const ColArgs none{};
-    const unsigned fs = 0xFFFFFFFFu;
     const int sel = (pcol.rounding << 1) | pcol.scale_up;
     switch (sel) {
-        case 0: hipLaunchKernelGGL((quant_col_kernel<0, false, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
-        case 1: hipLaunchKernelGGL((quant_col_kernel<0, true, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
-        case 2: hipLaunchKernelGGL((quant_col_kernel<1, false, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
-        default: hipLaunchKernelGGL((quant_col_kernel<1, true, false, true>), grid, dim3(kThreads), 0, st, a, none, fs); break;
+        case 0: hipLaunchKernelGGL((quant_dual_kernel<0, false>), grid, dim3(kThreads), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((quant_dual_kernel<0, true>), grid, dim3(kThreads), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((quant_dual_kernel<1, false>), grid, dim3(kThreads), 0, st, a); break;
+        default: hipLaunchKernelGGL((quant_dual_kernel<1, true>), grid, dim3(kThreads), 0, st, a); break;
     }
     return hipGetLastError();
 }
@@ -656,6 +830,7 @@ static ColArgs packed_args(const PackedSrc &src, int64_t R, int64_t C, const Qua
     a.src_codes = src.codes;
     a.src_scales = src.scales;
     a.src_gscale = src.gscale;
+    a.src_outer = src.outer;
     a.R = R;
     a.C = C;
     a.k = make_kargs(p, o);
@@ -667,7 +842,7 @@ hipError_t launch_requant_col(const PackedSrc &src, int64_t R, int64_t C, const 
 {
     if (R == 0 || C == 0) return hipSuccess;
     ColArgs a = packed_args(src, R, C, p, o), none{};
-    launch_col_t<true>(a, none, false, p.rounding, p.scale_up, st);
+    launch_colw<true>(a, none, false, p, st);
     return hipGetLastError();
 }
 
@@ -678,7 +853,7 @@ hipError_t launch_requant_col_pair(const PackedSrc &src0, int64_t R0, int64_t C0
     if (R0 == 0 || C0 == 0) return launch_requant_col(src1, R1, C1, p1, o1, st);
     if (R1 == 0 || C1 == 0) return launch_requant_col(src0, R0, C0, p0, o0, st);
     ColArgs a0 = packed_args(src0, R0, C0, p0, o0), a1 = packed_args(src1, R1, C1, p1, o1);
-    launch_col_t<true>(a0, a1, true, p0.rounding, p0.scale_up, st);
+    launch_colw<true>(a0, a1, true, p0, st);
     return hipGetLastError();
 }
 

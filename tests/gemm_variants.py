@@ -25,3 +25,22 @@ VARIANT_SHAPES = {
     (256, 256, True, False): (14086, 783, 256),
     (256, 256, True, True): (16564, 193, 3072),
 }
+
+# The same for operands with 1 x 128 outer blocks (K a multiple of 128; no 256 x 256 tile there: that mode keeps two
+# accumulator sets per wave).
+VARIANT_SHAPES_BLOCK128 = {
+    (128, 128, False, False): (13242, 73, 128),
+    (128, 128, False, True): (731, 137, 1152),
+    (128, 128, True, False): (16897, 2141, 512),
+    (128, 128, True, True): (13657, 41, 3584),
+    (128, 192, True, False): (181, 1495, 256),
+    (128, 192, True, True): (126, 2773, 2048),
+    (128, 256, False, False): (6452, 2450, 1408),
+    (128, 256, False, True): (6439, 171, 2944),
+    (128, 256, True, False): (2628, 2958, 512),
+    (128, 256, True, True): (10813, 206, 3072),
+    (256, 128, False, False): (18350, 263, 1408),
+    (256, 128, False, True): (4409, 281, 1920),
+    (256, 128, True, False): (6332, 2378, 512),
+    (256, 128, True, True): (3661, 225, 3584),
+}

@@ -105,7 +105,9 @@ def test_gemm_and_linear_reject_bad_arguments(lib):
     g = lambda a, b, out=FAKE, dt=0, ws=FAKE, wsb=1 << 30: lib.nvfp4_gemm_nt(C.byref(a), C.byref(b), out, dt, ws, wsb, None)
     assert g(A, _tensor(64, 128)) == -6
     assert g(_tensor(128, 80), _tensor(64, 80)) == -2      # K % 64
-    assert g(_tensor(128, 256, outer=1), Bt) == -3
+    assert g(_tensor(128, 256, outer=1), Bt) == -6         # operands in different outer modes
+    assert g(_tensor(128, 256, outer=2), Bt) == -3
+    assert g(_tensor(128, 320, outer=1), _tensor(64, 320, outer=1)) == -2   # K % 128 with 1 x 128 outer blocks
     assert g(A, Bt, out=None) == -1
     assert g(A, Bt, dt=3) == -3
     assert g(A, Bt, out=FAKE + 4) == -5
@@ -116,7 +118,8 @@ def test_gemm_and_linear_reject_bad_arguments(lib):
     fwd = lambda N, D, Cc, ws=FAKE, wsb=1 << 40, outer=0: lib.nvfp4_linear_fwd(
         FAKE, FAKE, N, D, Cc, FAKE, 0, C.byref(_tensor()), C.byref(_tensor()), outer, ws, wsb, None)
     assert fwd(128, 100, 64) == -2
-    assert fwd(128, 128, 64, outer=1) == -3
+    assert fwd(128, 128, 64, outer=2) == -3
+    assert fwd(128, 192, 64, outer=1) == -2                # D % 128 with 1 x 128 outer blocks
     assert fwd(128, 128, 64, wsb=8) == -4
     assert fwd(-1, 128, 64) == -2
     W = _tensor(64, 128)
@@ -171,7 +174,7 @@ def test_planner_and_workspace_accept_empty_products(lib):
     on a zero tile count (every linear-layer call sizes its workspace through this path)."""
     for M, N, K in [(0, 64, 128), (64, 0, 128), (64, 128, 0), (0, 0, 0)]:
         bm, bn, sp = C.c_int(), C.c_int(), C.c_int()
-        assert lib.nvfp4_gemm_plan(M, N, K, C.byref(bm), C.byref(bn), C.byref(sp)) == 0
+        assert lib.nvfp4_gemm_plan(M, N, K, 0, C.byref(bm), C.byref(bn), C.byref(sp)) == 0
         assert sp.value == 1
         assert lib.nvfp4_workspace_bytes(B.OP_GEMM, M, K, N, 0) == 0
     for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD_DX, B.OP_LINEAR_BWD_DW, B.OP_LINEAR_BWD):
@@ -190,6 +193,15 @@ def test_gemm_variant_table_reaches_every_kernel_instantiation():
         pm, pn, split = B.gemm_plan(M, N, K)
         assert (pm, pn, K % 256 == 0, split > 1) == (bm, bn, ps, sp), (M, N, K)
         assert M % 64 and N % 4
+    # operands with 1 x 128 outer blocks: three tiles x fetch x split, and the 128 x 192 tile with the paired fetch
+    from gemm_variants import VARIANT_SHAPES_BLOCK128
+    want = {(bm, bn, ps, sp) for bm, bn in tiles[:3] for ps in (False, True) for sp in (False, True)}
+    want |= {(128, 192, True, False), (128, 192, True, True)}
+    assert set(VARIANT_SHAPES_BLOCK128) == want
+    for (bm, bn, ps, sp), (M, N, K) in VARIANT_SHAPES_BLOCK128.items():
+        pm, pn, split = B.gemm_plan(M, N, K, B.OUTER_BLOCK128)
+        assert (pm, pn, K % 256 == 0, split > 1) == (bm, bn, ps, sp), (M, N, K)
+        assert M % 64 and N % 4 and K % 128 == 0
 
 
 def test_static_scratch_entry_rejects_bad_arguments_and_oversized_products(lib):
@@ -202,7 +214,7 @@ def test_static_scratch_entry_rejects_bad_arguments_and_oversized_products(lib):
     assert lib.nvfp4_gemm_nt_static(C.byref(ok), C.byref(ok), FAKE + 4, 0, None) == -5
     assert lib.nvfp4_gemm_nt_static(C.byref(ok), C.byref(_tensor(256, 576)), FAKE, 0, None) == -6
     assert lib.nvfp4_gemm_nt_static(C.byref(_tensor(256, 544)), C.byref(_tensor(256, 544)), FAKE, 0, None) == -2
-    assert lib.nvfp4_gemm_nt_static(C.byref(_tensor(256, 512, outer=1)), C.byref(ok), FAKE, 0, None) == -3
+    assert lib.nvfp4_gemm_nt_static(C.byref(_tensor(256, 512, outer=1)), C.byref(ok), FAKE, 0, None) == -6
     big = [(M, N, K) for (M, N, K) in ((3072, 3072, 65536), (2304, 4096, 65536), (1536, 8192, 32768), (4096, 3072, 262144))
            if B.workspace_bytes(B.OP_GEMM, M, K, N) > B.STATIC_SCRATCH_BYTES]
     assert big, "no candidate shape exceeds the static scratch array any more: extend the list"

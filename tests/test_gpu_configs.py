@@ -64,31 +64,32 @@ def product_ok(got_rows: torch.Tensor, ref, absref, what):
     assert np.all(err <= tol), "%s: err %.3e tol %.3e at %s" % (what, err[worst], tol[worst], worst)
 
 
-def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed):
+def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0):
     B = tj.binding
+    cfg = cfg + ("/block128" if outer else "")
     say("[%s %s] N=%d D=%d C=%d: inputs" % (cfg, name, N, D, C))
     Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed, kind)
     X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
-    ws = tj.alloc_workspace(max(tj.workspace_bytes(op, N, D, C) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD)))
-    Xq, Wq = tj.alloc_nvfp4(N, D), tj.alloc_nvfp4(C, D)
+    ws = tj.alloc_workspace(max(tj.workspace_bytes(op, N, D, C, outer) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD)))
+    Xq, Wq = tj.alloc_nvfp4(N, D, outer), tj.alloc_nvfp4(C, D, outer)
     Y = torch.empty((N, C), dtype=torch.bfloat16, device="cuda")
     dX = torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
     dW = torch.empty((C, D), dtype=torch.bfloat16, device="cuda")
-    tj.linear_fwd(X, W, B.OUT_BF16, Y=Y, Xq=Xq, Wq=Wq, ws=ws)
+    tj.linear_fwd(X, W, B.OUT_BF16, Y=Y, Xq=Xq, Wq=Wq, ws=ws, outer=outer)
     tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_BF16, dX=dX, dW=dW, ws=ws)
     torch.cuda.synchronize()
 
     say("[%s %s] oracle forward operands" % (cfg, name))
-    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb, outer=outer)
     same_bytes(Xq, oXq, "Q1(X)", check_amax=True)
     same_bytes(Wq, oWq, "Q2(W)", check_amax=True)
     say("[%s %s] oracle backward operands" % (cfg, name))
-    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, sr_seed, li)
-    same_bytes(tj.quantize(dY, 0, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 3), o3, "Q3(dY)")
-    same_bytes(tj.quantize(Wq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 4), o4, "Q4(W_hat)")
-    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, sr_seed, li)
-    same_bytes(tj.quantize(dY, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 5), o5, "Q5(dY^T)")
-    same_bytes(tj.quantize(Xq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 6), o6, "Q6(X_hat)")
+    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, sr_seed, li, outer=outer)
+    same_bytes(tj.quantize(dY, 0, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 3, outer=outer), o3, "Q3(dY)")
+    same_bytes(tj.quantize(Wq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 4, outer=outer), o4, "Q4(W_hat)")
+    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, sr_seed, li, outer=outer)
+    same_bytes(tj.quantize(dY, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 5, outer=outer), o5, "Q5(dY^T)")
+    same_bytes(tj.quantize(Xq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 6, outer=outer), o6, "Q6(X_hat)")
     dX1 = tj.linear_bwd_dx(dY, Wq, sr_seed, li, B.OUT_BF16)
     dW1 = tj.linear_bwd_dw(dY, Xq, sr_seed, li, B.OUT_BF16)
     torch.cuda.synchronize()
@@ -100,7 +101,7 @@ def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed):
         # the same layer with FP32 outputs: the 1e-3 bound is stated on the value before any bf16 rounding
         say("[%s %s] FP32-output run" % (cfg, name))
         del dX1, dW1
-        Y32, _, _ = tj.linear_fwd(X, W, B.OUT_F32, Xq=Xq, Wq=Wq, ws=ws)
+        Y32, _, _ = tj.linear_fwd(X, W, B.OUT_F32, Xq=Xq, Wq=Wq, ws=ws, outer=outer)
         dX32, dW32 = tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_F32, ws=ws)
         torch.cuda.synchronize()
         outs32 = {"Y": Y32, "dX": dX32, "dW": dW32}
@@ -127,6 +128,13 @@ def test_full_size_linear(cfg, li):
     run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed=0)
 
 
+@pytest.mark.parametrize("cfg,li", _cases("cfg1_single") + _cases("cfg2_block768") + _cases("cfg3_block1024") + _cases("cfg5_square8192"))
+def test_full_size_linear_block128(cfg, li):
+    """the same workloads with the paper's 1 x 128 outer blocks on every operand (no maximum pass anywhere)"""
+    name, N, D, C, seed, kind = wl.config_linears(cfg)[li]
+    run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed=0, outer=tj.binding.OUTER_BLOCK128)
+
+
 def test_quantizer_stress_full():
     """8192 x 8192 Student-t(3) x 0.1: row-wise nearest and column-wise stochastic (seed 7), every byte."""
     B = tj.binding
@@ -142,6 +150,9 @@ def test_quantizer_stress_full():
     row, col = tj.quantize_dual(x, B.ROUND_SR, seed=7, tensor_id_row=3, tensor_id_col=5)
     same_bytes(row, oracle.quantize_bf16(bits, 0, oracle.SR, seed=7, tensor_id=3), "dual row SR")
     same_bytes(col, oracle.quantize_bf16(bits, 1, oracle.SR, seed=7, tensor_id=5), "dual col SR")
+    say("[cfg4] column-wise stochastic, 1 x 128 outer blocks")
+    same_bytes(tj.quantize(x, 1, B.ROUND_SR, seed=7, tensor_id=5, outer=B.OUTER_BLOCK128),
+               oracle.quantize_bf16(bits, 1, oracle.SR, seed=7, tensor_id=5, outer=oracle.OUTER_BLOCK128), "col SR block128")
     say("[cfg4] row-wise stochastic, 1 x 128 outer blocks")
     same_bytes(tj.quantize(x, 0, B.ROUND_SR, seed=7, tensor_id=3, outer=B.OUTER_BLOCK128),
                oracle.quantize_bf16(bits, 0, oracle.SR, seed=7, tensor_id=3, outer=oracle.OUTER_BLOCK128), "row SR block128")

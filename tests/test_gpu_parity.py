@@ -181,6 +181,34 @@ def test_quant_col(shape, rounding):
     assert_same(got, ref, "col %s r%d" % (shape, rounding))
 
 
+@pytest.mark.parametrize("shape", [(128, 8), (256, 512), (384, 136), (1152, 1040), (2048, 72)])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_quant_col_block128_mode(shape, rounding):
+    """column-wise with the paper's 1 x 128 outer blocks (along the source's rows): single pass, no tensor maximum"""
+    bits = wl.student_t_bf16(shape, 3.0, 0.1, 450 + shape[1])
+    bits[:128, 0] = 0                  # an all-zero outer block
+    bits[16:32, 2] = 0                 # an all-zero inner block
+    ref = oracle.quantize_bf16(bits, 1, rounding, outer=oracle.OUTER_BLOCK128, seed=8, tensor_id=4)
+    got = tj.quantize(dev_bf16(bits), 1, rounding, outer=tj.binding.OUTER_BLOCK128, seed=8, tensor_id=4)
+    assert_same(got, ref, "col128 %s r%d" % (shape, rounding))
+
+
+@pytest.mark.parametrize("shape", [(128, 128), (256, 512), (384, 1152), (1024, 256)])
+@pytest.mark.parametrize("src_outer,out_outer", [(1, 1), (0, 1), (1, 0)])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_requant_col_outer_modes(shape, src_outer, out_outer, rounding):
+    """re-quantization of a packed tensor along its other axis with 1 x 128 outer blocks on the source, the output,
+    or both (the backward operands Q4 / Q6 of a layer whose operands carry the paper's outer scale)"""
+    bits = wl.normal_bf16(shape, 1.0, 460 + shape[0], 1e-2, 50.0)
+    bits[5, 128:256] = 0 if shape[1] >= 256 else bits[5, 128:256]
+    src_ref = oracle.quantize_bf16(bits, 0, 0, outer=src_outer)
+    ref = oracle.requantize(src_ref, 1, rounding, outer=out_outer, seed=17, tensor_id=6)
+    src = tj.quantize(dev_bf16(bits), 0, 0, outer=src_outer)
+    assert_same(src, src_ref, "source", check_amax=True)
+    got = tj.quantize(src, 1, rounding, outer=out_outer, seed=17, tensor_id=6)
+    assert_same(got, ref, "requant %s src%d out%d r%d" % (shape, src_outer, out_outer, rounding))
+
+
 @pytest.mark.parametrize("shape", [(256, 512), (16, 16), (144, 80), (1040, 144), (272, 1024), (528, 2064)])
 @pytest.mark.parametrize("rounding", [0, 1])
 def test_quantize_dual_equals_both_quantizations(shape, rounding):
@@ -303,6 +331,88 @@ def test_gemm_every_kernel_instantiation(key, shape, out_dtype):
     rows = np.unique(np.concatenate([[r for r in edge if 0 <= r < M], rng.choice(M, min(M, 24), replace=False)]))
     ref, absref = oracle.gemm_nt(A, B, rows_a=rows)
     check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm %dx%dx%d" % (M, N, K))
+
+
+def _block_operand(rows, K, seed, std):
+    """an operand with 1 x 128 outer blocks whose outer scales differ widely from block to block (each 128-block of each
+    row gets its own magnitude, 2^-6 .. 2^6 times the base law; a few blocks are all zero)"""
+    rng = np.random.default_rng(seed)
+    x = wl.bf16_to_f32(wl.normal_bf16((rows, K), std, seed, 1e-2, 30.0)).reshape(rows, K // 128, 128)
+    mag = np.exp2(rng.integers(-6, 7, (rows, K // 128, 1))).astype(np.float32)
+    mag[rng.random((rows, K // 128, 1)) < 0.02] = 0.0
+    return wl.f32_to_bf16((x * mag).reshape(rows, K))
+
+
+def _variant_cases_block128():
+    from gemm_variants import VARIANT_SHAPES_BLOCK128
+    cases, nsplit = [], 0
+    for key, shape in sorted(VARIANT_SHAPES_BLOCK128.items()):
+        nsplit += key[3]
+        for out_dtype in ((nsplit & 1,) if key[3] else (0, 1)):
+            cases.append(pytest.param(key, shape, out_dtype, id="b128-%dx%d-ps%d-split%d-out%d" % (*map(int, key), out_dtype)))
+    return cases
+
+
+@pytest.mark.parametrize("key,shape,out_dtype", _variant_cases_block128())
+def test_gemm_block128_every_kernel_instantiation(key, shape, out_dtype):
+    """The product on operands with the paper's 1 x 128 outer blocks (Sec. 2.2): every tile x scale fetch x split x output
+    variant of that mode, on ragged shapes, against the float64 product of the same dequantized operands."""
+    M, N, K = shape
+    O = tj.binding.OUTER_BLOCK128
+    pm, pn, split = tj.binding.gemm_plan(M, N, K, O)
+    assert (pm, pn, K % 256 == 0, split > 1) == key
+    A = oracle.quantize_bf16(_block_operand(M, K, 700 + N, 1.0), 0, 0, outer=oracle.OUTER_BLOCK128)
+    B = oracle.quantize_bf16(_block_operand(N, K, 701 + M, 0.02), 0, 1, outer=oracle.OUTER_BLOCK128, seed=6)
+    got = tj.gemm_nt(to_dev(A), to_dev(B), out_dtype)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(M * 31 + N)
+    edge = [0, M - 1, (M // pm) * pm - 1, (M // pm) * pm % M, min(M - 1, pm - 1), min(M - 1, pm)]
+    rows = np.unique(np.concatenate([[r for r in edge if 0 <= r < M], rng.choice(M, min(M, 24), replace=False)]))
+    ref, absref = oracle.gemm_nt(A, B, rows_a=rows)
+    check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm block128 %dx%dx%d" % (M, N, K))
+
+
+def test_gemm_block128_small_shapes_in_full_and_mode_mismatch():
+    O = oracle.OUTER_BLOCK128
+    for (M, N, K) in [(33, 20, 128), (130, 257, 384), (256, 512, 1024), (64, 64, 4096)]:
+        A = oracle.quantize_bf16(_block_operand(M, K, 720 + M, 1.0), 0, 0, outer=O)
+        B = oracle.quantize_bf16(_block_operand(N, K, 721 + N, 0.5), 0, 0, outer=O)
+        ref, absref = oracle.gemm_nt(A, B)
+        for out_dtype in (1, 0):
+            check_product(tj.gemm_nt(to_dev(A), to_dev(B), out_dtype), ref, absref, "block128 %dx%dx%d" % (M, N, K))
+    At = oracle.quantize_bf16(_block_operand(64, 256, 1, 1.0), 0, 0)
+    Bb = oracle.quantize_bf16(_block_operand(64, 256, 2, 1.0), 0, 0, outer=O)
+    with pytest.raises(tj.NVFP4Error) as e:
+        tj.gemm_nt(to_dev(At), to_dev(Bb), 1)
+    assert e.value.code == -6
+
+
+@pytest.mark.parametrize("N,D,C", [(256, 512, 384), (384, 128, 640), (1152, 256, 128)])
+def test_linear_block128_mode(N, D, C):
+    """The whole layer with the paper's 1 x 128 outer blocks on every operand: forward, the two separate backward calls
+    and the fused one; operands bit for bit, products within tolerance, no maximum pass anywhere."""
+    B = tj.binding
+    O = oracle.OUTER_BLOCK128
+    Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed=40 + N)
+    X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
+    Y, Xq, Wq = tj.linear_fwd(X, W, B.OUT_F32, outer=B.OUTER_BLOCK128)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb, outer=O)
+    assert_same(Xq, oXq, "Q1 block128", check_amax=True)
+    assert_same(Wq, oWq, "Q2 block128", check_amax=True)
+    check_product(Y, *oracle.gemm_nt(oXq, oWq), "Y block128")
+    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, 5, 2, outer=O)
+    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, 5, 2, outer=O)
+    assert_same(tj.quantize(dY, 0, B.ROUND_SR, seed=5, tensor_id=19, outer=B.OUTER_BLOCK128), o3, "Q3 block128")
+    assert_same(tj.quantize(Wq, 1, B.ROUND_SR, seed=5, tensor_id=20, outer=B.OUTER_BLOCK128), o4, "Q4 block128")
+    assert_same(tj.quantize(dY, 1, B.ROUND_SR, seed=5, tensor_id=21, outer=B.OUTER_BLOCK128), o5, "Q5 block128")
+    assert_same(tj.quantize(Xq, 1, B.ROUND_SR, seed=5, tensor_id=22, outer=B.OUTER_BLOCK128), o6, "Q6 block128")
+    dX = tj.linear_bwd_dx(dY, Wq, 5, 2, B.OUT_F32)
+    dW = tj.linear_bwd_dw(dY, Xq, 5, 2, B.OUT_F32)
+    check_product(dX, *oracle.gemm_nt(o3, o4), "dX block128")
+    check_product(dW, *oracle.gemm_nt(o5, o6), "dW block128")
+    dX2, dW2 = tj.linear_bwd(dY, Xq, Wq, 5, 2, B.OUT_F32)
+    torch.cuda.synchronize()
+    assert torch.equal(dX, dX2) and torch.equal(dW, dW2)
 
 
 def test_gemm_exact_on_integer_operands():
