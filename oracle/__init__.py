@@ -69,6 +69,10 @@ def lib():
         L.oracle_quantize_rows_slice.argtypes = [p, i64, i64, i32, i32, i32, u64, u32, i64, f32, p, p, p]
         L.oracle_rand22_fill.restype = None
         L.oracle_rand22_fill.argtypes = [u64, i64, p]
+        L.oracle_rht_sign.restype = i32
+        L.oracle_rht_sign.argtypes = [u64, u64]
+        L.oracle_rht16_rows.restype = i32
+        L.oracle_rht16_rows.argtypes = [p, i64, i64, u64]
         L.oracle_dequant_f32.restype = i32
         L.oracle_dequant_f32.argtypes = [p, p, p, i64, i64, i32, p]
         L.oracle_dequant_f64.restype = i32
@@ -116,10 +120,24 @@ def transpose_f32(x: np.ndarray) -> np.ndarray:
     return out
 
 
+def rht16(x: np.ndarray, seed: int, rht_id: int) -> np.ndarray:
+    """x S H_16 along the last axis of a float32 [rows, K] array (Sec. 4.1); the signs are those of stream
+    (seed, rht_id) and depend on the position along K only."""
+    x = np.array(x, dtype=np.float32, order="C", copy=True)
+    rows, K = x.shape
+    rc = lib().oracle_rht16_rows(_ptr(x), rows, K, lib().oracle_stream_key(seed, rht_id))
+    if rc != 0:
+        raise ValueError("oracle_rht16_rows: bad shape")
+    return x
+
+
 def quantize_f32(x: np.ndarray, rounding: int, scale_round: int = SCALE_DEFAULT,
-                 outer: int = OUTER_TENSOR, seed: int = 0, tensor_id: int = 0) -> NVFP4:
-    """Quantize a float32 [rows, K] view along K (Sec. 2.2)."""
+                 outer: int = OUTER_TENSOR, seed: int = 0, tensor_id: int = 0, rht_id=None) -> NVFP4:
+    """Quantize a float32 [rows, K] view along K (Sec. 2.2); with rht_id, after the random Hadamard transform of
+    Sec. 4.1 along K (signs of stream (seed, rht_id))."""
     x = np.ascontiguousarray(x, dtype=np.float32)
+    if rht_id is not None:
+        x = rht16(x, seed, rht_id)
     rows, K = x.shape
     codes = np.zeros((rows, K // 2), dtype=np.uint8)
     scales = np.zeros((rows, K // 16), dtype=np.uint8)
@@ -219,15 +237,24 @@ def linear_fwd(X_bits, W_bits, outer: int = OUTER_TENSOR):
     return Xq, Wq
 
 
-def linear_bwd_dx_operands(dY_bits, Wq: NVFP4, seed: int, layer_id: int, outer: int = OUTER_TENSOR):
-    """dX = Q3_S(dY) x Q4_S(W_hat): returns (dYq [N, C], Wq' [D, C]), both grouped along C."""
-    dYq = quantize_bf16(dY_bits, 0, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 3))
-    Wq2 = requantize(Wq, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 4))
+def rht_id(layer_id: int, product: str):
+    """Stream id of the random signs of a layer's backward product (Sec. 4.1): "dx" (signs along C) or "dw" (along N)."""
+    return layer_id * 8 + (7 if product == "dx" else 0)
+
+
+def linear_bwd_dx_operands(dY_bits, Wq: NVFP4, seed: int, layer_id: int, outer: int = OUTER_TENSOR, rht: bool = False):
+    """dX = Q3_S(dY) x Q4_S(W_hat): returns (dYq [N, C], Wq' [D, C]), both grouped along C; with rht, both operands
+    are transformed along C with the same signs first (Sec. 4.1/4.2: Q3(dY S H), Q4(H^T S^T W_hat))."""
+    rid = rht_id(layer_id, "dx") if rht else None
+    dYq = quantize_bf16(dY_bits, 0, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 3), rht_id=rid)
+    Wq2 = requantize(Wq, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 4), rht_id=rid)
     return dYq, Wq2
 
 
-def linear_bwd_dw_operands(dY_bits, Xq: NVFP4, seed: int, layer_id: int, outer: int = OUTER_TENSOR):
-    """dW = Q5_S(dY^T) x Q6_S(X_hat): returns (dYq' [C, N], Xq' [D, N]), both grouped along N."""
-    dYq = quantize_bf16(dY_bits, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 5))
-    Xq2 = requantize(Xq, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 6))
+def linear_bwd_dw_operands(dY_bits, Xq: NVFP4, seed: int, layer_id: int, outer: int = OUTER_TENSOR, rht: bool = False):
+    """dW = Q5_S(dY^T) x Q6_S(X_hat): returns (dYq' [C, N], Xq' [D, N]), both grouped along N; with rht, both are
+    transformed along N with the same signs first."""
+    rid = rht_id(layer_id, "dw") if rht else None
+    dYq = quantize_bf16(dY_bits, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 5), rht_id=rid)
+    Xq2 = requantize(Xq, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 6), rht_id=rid)
     return dYq, Xq2

@@ -51,8 +51,17 @@
  *       Element k of a row sits in byte k/2, even k in the low nibble.
  *   R8  Re-quantizing an NVFP4 tensor (Q4, Q6 of Sec. 2.3) starts from its
  *       binary32 dequantized value  x = RN( (P * S_b) * S_g ).
+ *   R12 Random Hadamard transform (Sec. 4.1, block size 16): x <- x S H along the
+ *       grouped axis, before any scale is taken.  S: the sign of position k (the
+ *       same for every row, and for both operands of a product) is one bit of
+ *       the counter-based generator of R6 under a key of its own: bit
+ *       (15 + ((k mod 32) div 2) + 16 (k mod 2)) mod 32 of the 32-bit word of
+ *       counter k div 32 (every bit of a word serves exactly one position).
+ *       H = H_16 (Sylvester order, entries +-1/4), evaluated in binary32 as the
+ *       four butterfly stages with strides 1, 2, 4, 8 in that order, one
+ *       rounding per addition, then one multiplication by 1/4 (exact).
  *
- * Parity status: R1, R6, R7 are not fixed by the paper ("parity unpinned" by
+ * Parity status: R1, R6, R7, R12 (which bits, which summation order) are not fixed by the paper ("parity unpinned" by
  * the paper itself); they are pinned by the property tests in tests/ (grid
  * membership, exact round trips, scale/absmax invariants, closed-form SR
  * probabilities, unbiasedness, brute-force GEMMs).
@@ -182,6 +191,40 @@ int64_t oracle_round_sr_count_up(float a, int *lower_index)
     }
     *lower_index = base;
     return ups;
+}
+
+/* ------------------------------------------------------------------- RHT -- */
+
+/* R12: sign of position k along the grouped axis (1 = flipped) */
+int oracle_rht_sign(uint64_t k, uint64_t key)
+{
+    uint32_t w = oracle_quad_bits((uint32_t)(k >> 5), key);
+    unsigned bit = (unsigned)((15 + ((k & 31) >> 1) + 16 * (k & 1)) & 31);
+    return (int)((w >> bit) & 1u);
+}
+
+/* Sec. 4.1: x <- x S H_16 on every aligned run of 16 along K, in place; x is [rows][K] (R12) */
+int oracle_rht16_rows(float *x, int64_t rows, int64_t K, uint64_t key)
+{
+    if (rows < 0 || K < 0 || K % 16) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t b = 0; b < K / 16; ++b) {
+            volatile float v[16];
+            for (int i = 0; i < 16; ++i) {
+                float xi = x[r * K + b * 16 + i];
+                v[i] = oracle_rht_sign((uint64_t)(b * 16 + i), key) ? -xi : xi;
+            }
+            for (int h = 1; h < 16; h <<= 1)                     /* H_2d = [H_d H_d; H_d -H_d] / sqrt 2, unnormalised */
+                for (int i = 0; i < 16; ++i)
+                    if (!(i & h)) {
+                        float a = v[i], c = v[i + h];
+                        v[i] = a + c;
+                        v[i + h] = a - c;
+                    }
+            for (int i = 0; i < 16; ++i) x[r * K + b * 16 + i] = v[i] * 0.25f;   /* (1 / sqrt 2)^4 */
+        }
+    return 0;
 }
 
 /* ------------------------------------------------------------- quantizer -- */

@@ -294,3 +294,92 @@ def test_quad_draws_share_bits_only_below_their_leading_byte_and_the_joint_law_i
         for j in range(i + 1, 4):
             a, b = u[:, i] >= (1 << 21), u[:, j] >= (3 << 20)
             assert abs(np.mean(a & b) - np.mean(a) * np.mean(b)) < noise, (i, j)
+
+
+# ------------------------------------------------------------------------------------------ R12 (Sec. 4.1)
+
+def _h16():
+    H = np.array([[1.0]])
+    for _ in range(4):
+        H = np.block([[H, H], [H, -H]])                         # the paper's recursion, the four factors 1 / sqrt 2 ...
+    return H / 4.0                                              # ... collected: (1 / sqrt 2)^4 = 1 / 4 exactly
+
+
+def _signs(K, seed, rid):
+    L = oracle.lib()
+    key = L.oracle_stream_key(seed, rid)
+    return np.array([-1.0 if L.oracle_rht_sign(k, key) else 1.0 for k in range(K)])
+
+
+def test_rht_is_x_s_h_block_diagonal():
+    """Sec. 4.1: A' = A S_n H_n with H_n = diag{H_16, ...} and S_n a random diagonal of +-1.  The oracle's binary32
+    butterflies against that matrix product in binary64: equal on small integers (every sum exact), within a few
+    roundings otherwise; the signs depend on the position along K only."""
+    rng = np.random.default_rng(31)
+    K, rows = 96, 20
+    S = _signs(K, 5, 7)
+    H = np.kron(np.eye(K // 16), _h16())
+    assert np.allclose(H @ H.T, np.eye(K)) and np.allclose(H, H.T)
+    xi = rng.integers(-8, 9, (rows, K)).astype(np.float32) * 4          # multiples of 4: the final 1/4 stays exact
+    assert np.array_equal(oracle.rht16(xi, 5, 7).astype(np.float64), (xi.astype(np.float64) * S) @ H)
+    x = wl.bf16_to_f32(wl.normal_bf16((rows, K), 1.0, 32, 1e-2, 50.0))
+    got = oracle.rht16(x, 5, 7).astype(np.float64)
+    want = (x.astype(np.float64) * S) @ H
+    bound = 5 * 2.0 ** -24 * 0.25 * np.abs(x.astype(np.float64)).reshape(rows, K // 16, 16).sum(axis=2).repeat(16, axis=1)
+    assert np.all(np.abs(got - want) <= bound + 1e-300)
+    # a second row, another seed: same positions flip for every row of one stream, other positions for another stream
+    assert np.array_equal(np.sign(oracle.rht16(np.ones((3, K), np.float32), 5, 7)), np.sign(np.tile((S @ H), (3, 1))))
+    assert not np.array_equal(_signs(K, 5, 7), _signs(K, 6, 7)) and not np.array_equal(_signs(K, 5, 7), _signs(K, 5, 0))
+
+
+def test_rht_on_both_operands_leaves_the_product_unchanged():
+    """Sec. 4.1: A B^T = (A S H)(B S H)^T since S and H are orthogonal: on the unquantized operands, in binary64 of
+    the oracle's binary32 output, to rounding."""
+    A = wl.bf16_to_f32(wl.outlier_channel_bf16(24, 256, 41))
+    B = wl.bf16_to_f32(wl.normal_bf16((40, 256), 0.02, 42))
+    ref = A.astype(np.float64) @ B.astype(np.float64).T
+    At, Bt = oracle.rht16(A, 9, 15).astype(np.float64), oracle.rht16(B, 9, 15).astype(np.float64)
+    scale = np.abs(A.astype(np.float64)) @ np.abs(B.astype(np.float64)).T
+    assert np.all(np.abs(At @ Bt.T - ref) <= 1e-5 * scale)
+    # different signs on the two sides do change it
+    Bo = oracle.rht16(B, 9, 16).astype(np.float64)
+    assert np.abs(At @ Bo.T - ref).max() > 1e-2 * np.abs(ref).max()
+
+
+def test_rht_sign_bits_use_every_bit_of_a_word_once_and_are_balanced():
+    L = oracle.lib()
+    key = L.oracle_stream_key(77, 7)
+    for wi in (0, 1, 5):
+        w = L.oracle_quad_bits(wi, key)
+        bits = [L.oracle_rht_sign(32 * wi + k, key) for k in range(32)]
+        pos = [(15 + (k >> 1) + 16 * (k & 1)) & 31 for k in range(32)]
+        assert sorted(pos) == list(range(32))
+        assert bits == [(w >> p) & 1 for p in pos]
+    s = np.array([L.oracle_rht_sign(k, key) for k in range(1 << 14)])
+    assert abs(s.mean() - 0.5) < 5 * 0.5 / np.sqrt(len(s))
+    assert abs(np.corrcoef(s[:-1], s[1:])[0, 1]) < 0.05 and abs(np.corrcoef(s[:-16], s[16:])[0, 1]) < 0.05
+
+
+def test_rht_spreads_an_outlier_and_the_quantized_backward_products_stay_unbiased():
+    """What Sec. 4.1 is for: one huge entry in a group of 16 forces a scale under which the others vanish; after the
+    transform the group is flat.  And the layer's backward products with the transform on both operands
+    (1 x 128 outer blocks, stochastic rounding) are still unbiased estimates of the product of the aligned tensors."""
+    x = np.full((1, 16), 0.01, np.float32)
+    x[0, 3] = 100.0
+    t = oracle.rht16(x, 1, 7)
+    assert np.abs(t).max() / np.abs(t).min() < 1.01 and np.abs(x).max() / np.abs(x).min() > 1e3
+    N, D, C = 128, 128, 128
+    Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed=3)
+    O = oracle.OUTER_BLOCK128
+    Xq, Wq = oracle.linear_fwd(Xb, Wb, outer=O)
+    dY = wl.bf16_to_f32(dYb).astype(np.float64)
+    ref_dx = dY @ oracle.dequant_f64(Wq)
+    acc = np.zeros_like(ref_dx)
+    n = 24
+    for seed in range(n):
+        a, b = oracle.linear_bwd_dx_operands(dYb, Wq, seed, 1, outer=O, rht=True)
+        acc += oracle.gemm_nt(a, b)[0]
+    err_mean = np.abs(acc / n - ref_dx).mean()
+    a, b = oracle.linear_bwd_dx_operands(dYb, Wq, 0, 1, outer=O, rht=True)
+    err_one = np.abs(oracle.gemm_nt(a, b)[0] - ref_dx).mean()
+    assert err_mean < 0.45 * err_one                          # averaging seeds shrinks the error (~ 1 / sqrt n): no bias floor
