@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--outer", default="tensor", choices=["tensor", "block128"],
                     help="outer scale of every operand: per tensor, or the paper's 1 x 128 blocks")
+    ap.add_argument("--rht", action="store_true",
+                    help="random Hadamard transform (block 16) on both operands of both backward products; needs --outer block128")
     ap.add_argument("--no-extras", action="store_true", help="skip the side measurements (other workloads, quantizer bandwidth)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -53,9 +55,9 @@ def dev_bf16(torch, np, bits, dev):
 class Workload:
     """Resident inputs, contexts, outputs and workspaces of every linear of one workload, and its step."""
 
-    def __init__(self, tj, wl, np, torch, dev, name, outer):
+    def __init__(self, tj, wl, np, torch, dev, name, outer, rht=False):
         B = tj.binding
-        self.tj, self.B, self.name, self.outer = tj, B, name, outer
+        self.tj, self.B, self.name, self.outer, self.rht = tj, B, name, outer, rht
         self.layers = []
         for li, (lname, N, D, C, seed, kind) in enumerate(wl.config_linears(name)):
             Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed, kind)
@@ -84,7 +86,7 @@ class Workload:
         for L in self.layers:
             tj.linear_fwd(L["X"], L["W"], B.OUT_BF16, Y=L["Y"], Xq=L["Xq"], Wq=L["Wq"], ws=L["ws"], outer=self.outer)
         for L in reversed(self.layers):
-            tj.linear_bwd(L["dY"], L["Xq"], L["Wq"], sr_seed, L["li"], B.OUT_BF16, dX=L["dX"], dW=L["dW"], ws=L["ws"])
+            tj.linear_bwd(L["dY"], L["Xq"], L["Wq"], sr_seed, L["li"], B.OUT_BF16, dX=L["dX"], dW=L["dW"], ws=L["ws"], rht=self.rht)
 
     def time_steps(self, torch, steps, warmup):
         for i in range(warmup):
@@ -148,7 +150,10 @@ def main():
         print(json.dumps({"quantizer_launches_each": args.quantizers + 3, "lines": res}))
         return
 
-    w = Workload(tj, wl, np, torch, dev, args.workload, outer)
+    if args.rht and outer != B.OUTER_BLOCK128:
+        print("bench.py: --rht needs --outer block128", file=sys.stderr)
+        sys.exit(2)
+    w = Workload(tj, wl, np, torch, dev, args.workload, outer, args.rht)
     ms_per_step = w.time_steps(torch, args.steps, args.warmup)
     value = w.flops / (ms_per_step * 1e-3) / 1e12
     layers = w.layers
@@ -201,6 +206,7 @@ def main():
            "config": {"workload": args.workload, "tokens": layers[0]["N"],
                       "linears": [[L["name"], L["D"], L["C"]] for L in layers],
                       "outer_scale": "per-tensor" if outer == B.OUTER_TENSOR else "1x128 blocks",
+                      "rht": bool(args.rht),
                       "flops_per_step": w.flops},
            "frac_of_mfma_peak": round(value / MFMA_F16_PEAK_TFLOPS, 4),
            "frac_of_roofline_lower_bound": round(w.t_min * 1e3 / ms_per_step, 4),
@@ -255,6 +261,10 @@ def quantizer_lines(tj, wl, np, torch, dev, warm=300, reps=200):
                                                                          outer=B.OUTER_BLOCK128, ws=ws)),
         "col_sr_block128_single_pass": (alg_bytes, lambda i: tj.quantize(bufs[i % 4], 1, B.ROUND_SR, outs128[i % 2], seed=7,
                                                                          outer=B.OUTER_BLOCK128, ws=ws)),
+        "row_sr_block128_rht": (alg_bytes, lambda i: tj.quantize(bufs[i % 4], 0, B.ROUND_SR, outs128[i % 2], seed=7,
+                                                                 outer=B.OUTER_BLOCK128, ws=ws, rht_id=7)),
+        "col_sr_block128_rht": (alg_bytes, lambda i: tj.quantize(bufs[i % 4], 1, B.ROUND_SR, outs128[i % 2], seed=7,
+                                                                 outer=B.OUTER_BLOCK128, ws=ws, rht_id=0)),
         # both backward operands of one tensor from a single read: 2 B in + 2 x 0.5625 B out per element
         "dual_row_col_sr_amax_given": (dual_bytes, lambda i: tj.quantize_dual(
             bufs[i % 4], B.ROUND_SR, outs[0], outs[1], seed=7, tensor_id_row=3, tensor_id_col=5, amax_in=amax, ws=ws)),

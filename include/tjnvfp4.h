@@ -99,6 +99,11 @@ typedef struct nvfp4_qcfg {
                               output's own [rows x K] view) depend only on (seed, tensor_id, e) */
     uint64_t seed;
     const float *amax_in;  /* device [1], optional, TENSOR mode: max |src| if the caller already has it */
+    int32_t  rht;          /* 1: random Hadamard transform of Sec. 4.1 first: every aligned run of 16 along the grouped
+                              axis is multiplied by S H_16 (random signs, then the 16 x 16 Hadamard matrix), and the
+                              result is what gets quantized.  Provided with NVFP4_OUTER_BLOCK128 (ENUM otherwise). */
+    uint32_t rht_id;       /* stream id of the signs: sign of position k along the grouped axis depends only on
+                              (seed, rht_id, k); the two operands of a product must use the same */
 } nvfp4_qcfg;
 
 /*
@@ -166,18 +171,21 @@ int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t
 /*
  * Input gradient (Sec. 2.3, second line): dX [N x D] = Q3_S(dY) x Q4_S(W_hat); dY [N x C] bf16, W_hat = Wq_ctx of
  * the forward call, both re-grouped along C with stochastic rounding.  Streams: tensor ids layer_id*8+3 and +4.
+ * rht = 1 (Sec. 4.1 / 4.2; contexts with 1 x 128 outer blocks only): both operands are first transformed along C,
+ * dX = Q3(dY S H) x Q4(H^T S^T W_hat), signs of stream layer_id*8+7.
  */
 int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D, int64_t C,
-                        void *dX, int out_dtype, uint64_t seed, uint32_t layer_id,
+                        void *dX, int out_dtype, uint64_t seed, uint32_t layer_id, int rht,
                         void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Weight gradient (Sec. 2.3, third line): dW [C x D] = Q5_S(dY^T) x Q6_S(X_hat); both operands re-grouped along N
- * with stochastic rounding.  Streams: tensor ids layer_id*8+5 and +6.
+ * with stochastic rounding.  Streams: tensor ids layer_id*8+5 and +6.  rht = 1: both operands are first transformed
+ * along N, dW = Q5(dY^T S H) x Q6(H^T S^T X_hat), signs of stream layer_id*8+0.
  * Limits: N % 64 == 0 (N % 128 == 0 in BLOCK128 mode) and N <= 2^22 (reduction length); C % 8 == 0; D % 16 == 0.
  */
 int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C,
-                        void *dW, int out_dtype, uint64_t seed, uint32_t layer_id,
+                        void *dW, int out_dtype, uint64_t seed, uint32_t layer_id, int rht,
                         void *ws, size_t ws_bytes, void *stream);
 
 /*
@@ -189,7 +197,7 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
  */
 int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx,
                      int64_t N, int64_t D, int64_t C, void *dX, void *dW, int out_dtype,
-                     uint64_t seed, uint32_t layer_id, void *ws, size_t ws_bytes, void *stream);
+                     uint64_t seed, uint32_t layer_id, int rht, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Scratch bytes an operation needs.  op = NVFP4_OP_*.  QUANTIZE: (N, D) = (R, C) of the source, C ignored.

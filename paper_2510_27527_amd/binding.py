@@ -41,7 +41,8 @@ class CTensor(C.Structure):
 
 class CQcfg(C.Structure):
     _fields_ = [("rounding", C.c_int32), ("scale_round", C.c_int32), ("outer_mode", C.c_int32),
-                ("tensor_id", C.c_uint32), ("seed", C.c_uint64), ("amax_in", C.c_void_p)]
+                ("tensor_id", C.c_uint32), ("seed", C.c_uint64), ("amax_in", C.c_void_p), ("rht", C.c_int32),
+                ("rht_id", C.c_uint32)]
 
 
 _lib = None
@@ -68,12 +69,12 @@ def lib():
         L.nvfp4_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, i32, C.POINTER(CTensor), C.POINTER(CTensor),
                                        i32, vp, sz, vp]
         L.nvfp4_linear_bwd_dx.restype = i32
-        L.nvfp4_linear_bwd_dx.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, vp, sz, vp]
+        L.nvfp4_linear_bwd_dx.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, i32, vp, sz, vp]
         L.nvfp4_linear_bwd_dw.restype = i32
-        L.nvfp4_linear_bwd_dw.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, vp, sz, vp]
+        L.nvfp4_linear_bwd_dw.argtypes = [vp, C.POINTER(CTensor), i64, i64, i64, vp, i32, u64, u32, i32, vp, sz, vp]
         L.nvfp4_linear_bwd.restype = i32
         L.nvfp4_linear_bwd.argtypes = [vp, C.POINTER(CTensor), C.POINTER(CTensor), i64, i64, i64, vp, vp, i32, u64, u32,
-                                       vp, sz, vp]
+                                       i32, vp, sz, vp]
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
         L.nvfp4_gemm_plan.restype = i32
@@ -167,7 +168,7 @@ def amax_bf16(src: torch.Tensor, ws: torch.Tensor) -> torch.Tensor:
 
 def quantize(src, axis: int, rounding: int, out: Optional[NVFP4Tensor] = None, *, scale_round: int = SCALE_DEFAULT,
              outer: int = OUTER_TENSOR, seed: int = 0, tensor_id: int = 0, amax_in: Optional[torch.Tensor] = None,
-             ws: Optional[torch.Tensor] = None) -> NVFP4Tensor:
+             ws: Optional[torch.Tensor] = None, rht_id: Optional[int] = None) -> NVFP4Tensor:
     """nvfp4_quantize: src is a bf16 [R, C] tensor or an NVFP4Tensor."""
     if isinstance(src, NVFP4Tensor):
         kind, R, Cc = SRC_NVFP4, src.rows, src.K
@@ -184,7 +185,7 @@ def quantize(src, axis: int, rounding: int, out: Optional[NVFP4Tensor] = None, *
         out = alloc_nvfp4(rows, K, outer, dev)
     if ws is None:
         ws = alloc_workspace(workspace_bytes(OP_QUANTIZE, R, Cc, 0, outer), dev)
-    cfg = CQcfg(rounding, scale_round, outer, tensor_id, seed, _ptr(amax_in))
+    cfg = CQcfg(rounding, scale_round, outer, tensor_id, seed, _ptr(amax_in), 0 if rht_id is None else 1, rht_id or 0)
     co = out.c_struct()
     rc = lib().nvfp4_quantize(src_arg, kind, R, Cc, axis, C.byref(cfg), C.byref(co), _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_quantize")
@@ -206,7 +207,7 @@ def quantize_dual(src: torch.Tensor, rounding: int, out_row: Optional[NVFP4Tenso
         out_col = alloc_nvfp4(Cc, R, OUTER_TENSOR, dev)
     if ws is None:
         ws = alloc_workspace(workspace_bytes(OP_QUANTIZE, R, Cc, 0, OUTER_TENSOR), dev)
-    cfg = CQcfg(rounding, scale_round, OUTER_TENSOR, tensor_id_row, seed, _ptr(amax_in))
+    cfg = CQcfg(rounding, scale_round, OUTER_TENSOR, tensor_id_row, seed, _ptr(amax_in), 0, 0)
     cr, cc = out_row.c_struct(), out_col.c_struct()
     rc = lib().nvfp4_quantize_dual(_ptr(src), R, Cc, C.byref(cfg), tensor_id_col, C.byref(cr), C.byref(cc), _ptr(ws),
                                    ws.numel(), _stream())
@@ -279,7 +280,7 @@ def linear_fwd(X: torch.Tensor, W: torch.Tensor, out_dtype: int = OUT_BF16, *, Y
 
 
 def linear_bwd_dx(dY: torch.Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
-                  dX: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+                  dX: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, rht: bool = False) -> torch.Tensor:
     _check_bf16(dY, "dY")
     N, Cc = dY.shape
     D = Wq.K
@@ -288,14 +289,14 @@ def linear_bwd_dx(dY: torch.Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, o
     _check_out(dX, (N, D), out_dtype, "dX")
     ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DX, N, D, Cc, Wq.outer), dev) if ws is None else ws
     cw = Wq.c_struct()
-    rc = lib().nvfp4_linear_bwd_dx(_ptr(dY), C.byref(cw), N, D, Cc, _ptr(dX), out_dtype, seed, layer_id,
+    rc = lib().nvfp4_linear_bwd_dx(_ptr(dY), C.byref(cw), N, D, Cc, _ptr(dX), out_dtype, seed, layer_id, int(rht),
                                    _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_linear_bwd_dx")
     return dX
 
 
 def linear_bwd_dw(dY: torch.Tensor, Xq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
-                  dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+                  dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, rht: bool = False) -> torch.Tensor:
     _check_bf16(dY, "dY")
     N, Cc = dY.shape
     D = Xq.K
@@ -304,14 +305,15 @@ def linear_bwd_dw(dY: torch.Tensor, Xq: NVFP4Tensor, seed: int, layer_id: int, o
     _check_out(dW, (Cc, D), out_dtype, "dW")
     ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD_DW, N, D, Cc, Xq.outer), dev) if ws is None else ws
     cx = Xq.c_struct()
-    rc = lib().nvfp4_linear_bwd_dw(_ptr(dY), C.byref(cx), N, D, Cc, _ptr(dW), out_dtype, seed, layer_id,
+    rc = lib().nvfp4_linear_bwd_dw(_ptr(dY), C.byref(cx), N, D, Cc, _ptr(dW), out_dtype, seed, layer_id, int(rht),
                                    _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_linear_bwd_dw")
     return dW
 
 
 def linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
-               dX: Optional[torch.Tensor] = None, dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+               dX: Optional[torch.Tensor] = None, dW: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+               rht: bool = False):
     """nvfp4_linear_bwd: both gradients, dY read once for its maximum and once for both quantizations."""
     _check_bf16(dY, "dY")
     N, Cc = dY.shape
@@ -324,6 +326,6 @@ def linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, la
     ws = alloc_workspace(workspace_bytes(OP_LINEAR_BWD, N, D, Cc, Xq.outer), dev) if ws is None else ws
     cx, cw = Xq.c_struct(), Wq.c_struct()
     rc = lib().nvfp4_linear_bwd(_ptr(dY), C.byref(cx), C.byref(cw), N, D, Cc, _ptr(dX), _ptr(dW), out_dtype, seed,
-                                layer_id, _ptr(ws), ws.numel(), _stream())
+                                layer_id, int(rht), _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_linear_bwd")
     return dX, dW

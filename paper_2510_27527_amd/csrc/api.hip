@@ -99,7 +99,7 @@ struct QuantPlan {
     int src_kind, axis;
     int64_t R, C;
     int64_t out_rows, out_K;
-    int rounding, scale_up, outer;
+    int rounding, scale_up, outer, rht;
     bool need_partials;
 };
 
@@ -123,6 +123,9 @@ int plan_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis,
     pl->scale_up = cfg->scale_round == NVFP4_SCALE_DEFAULT ? (cfg->rounding == NVFP4_ROUND_SR)
                                                            : (cfg->scale_round == NVFP4_SCALE_UP);
     pl->outer = cfg->outer_mode;
+    pl->rht = cfg->rht;
+    if (cfg->rht != 0 && cfg->rht != 1) return NVFP4_ERR_ENUM;
+    if (cfg->rht && pl->outer != NVFP4_OUTER_BLOCK128) return NVFP4_ERR_ENUM;   // the transform comes with 1 x 128 outer blocks
     int rc = check_shape(pl->out_rows, pl->out_K, pl->outer);
     if (rc) return rc;
     rc = check_tensor_ptrs(out);
@@ -148,6 +151,14 @@ int plan_quantize(const void *src, int src_kind, int64_t R, int64_t C, int axis,
     return NVFP4_OK;
 }
 
+void set_rht(QuantParams &p, const QuantPlan &pl, const nvfp4_qcfg *cfg)
+{
+    p.rht = pl.rht;
+    const uint64_t key = stream_key(cfg->seed, cfg->rht_id);
+    p.r0 = (uint32_t)key;
+    p.r1 = (uint32_t)(key >> 32);
+}
+
 int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nvfp4_tensor *out, float *partials,
                  hipStream_t st)
 {
@@ -158,6 +169,7 @@ int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nv
     const uint64_t key = stream_key(cfg->seed, cfg->tensor_id);
     p.k0 = (uint32_t)key;
     p.k1 = (uint32_t)(key >> 32);
+    set_rht(p, pl, cfg);
     QuantOut o{out->codes, out->scales, out->gscale, out->amax_deq};
     out->rows = pl.out_rows;
     out->K = pl.out_K;
@@ -165,7 +177,7 @@ int run_quantize(const void *src, const QuantPlan &pl, const nvfp4_qcfg *cfg, nv
     if (pl.out_rows == 0 || pl.out_K == 0) return NVFP4_OK;
     hipError_t e;
     if (pl.src_kind == NVFP4_SRC_BF16) {
-        if (pl.rounding != NVFP4_ROUND_RTN) o.amax_deq = nullptr;   // only forward operands are re-quantized
+        if (pl.rounding != NVFP4_ROUND_RTN || pl.rht) o.amax_deq = nullptr;   // only forward operands are re-quantized
         bool zeroed = o.amax_deq == nullptr;
         if (pl.outer == NVFP4_OUTER_TENSOR) {
             if (cfg->amax_in) {
@@ -206,6 +218,7 @@ QuantParams params_of(const QuantPlan &pl, const nvfp4_qcfg *cfg)
     const uint64_t key = stream_key(cfg->seed, cfg->tensor_id);
     p.k0 = (uint32_t)key;
     p.k1 = (uint32_t)(key >> 32);
+    set_rht(p, pl, cfg);
     return p;
 }
 
@@ -258,7 +271,7 @@ int run_requant_pair(const nvfp4_tensor *s0, const QuantPlan &pl0, const nvfp4_q
     QuantParams p0 = params_of(pl0, c0), p1 = params_of(pl1, c1);
     p0.amax_scalar = pl0.outer == NVFP4_OUTER_TENSOR ? (c0->amax_in ? c0->amax_in : s0->amax_deq) : nullptr;
     p1.amax_scalar = pl1.outer == NVFP4_OUTER_TENSOR ? (c1->amax_in ? c1->amax_in : s1->amax_deq) : nullptr;
-    if (p0.rounding != p1.rounding || p0.scale_up != p1.scale_up || p0.outer != p1.outer) {
+    if (p0.rounding != p1.rounding || p0.scale_up != p1.scale_up || p0.outer != p1.outer || p0.rht != p1.rht) {
         const int rc = run_quantize(s0, pl0, c0, out0, nullptr, st);
         return rc ? rc : run_quantize(s1, pl1, c1, out1, nullptr, st);
     }
@@ -505,18 +518,20 @@ int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t
 }
 
 // stochastic-rounding settings of backward quantizer Q<k> of a layer (k = 3..6), in the forward operands' outer mode
-static nvfp4_qcfg bwd_cfg(uint64_t seed, uint32_t layer_id, int k, int outer)
+static nvfp4_qcfg bwd_cfg(uint64_t seed, uint32_t layer_id, int k, int outer, int rht)
 {
     nvfp4_qcfg c{};
     c.rounding = NVFP4_ROUND_SR;
     c.outer_mode = outer;
     c.seed = seed;
     c.tensor_id = layer_id * 8u + (uint32_t)k;
+    c.rht = rht;
+    c.rht_id = layer_id * 8u + (k <= 4 ? 7u : 0u);      // Q3, Q4: the signs of the dX product; Q5, Q6: of the dW product
     return c;
 }
 
 int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D, int64_t C, void *dX,
-                        int out_dtype, uint64_t seed, uint32_t layer_id, void *ws, size_t ws_bytes, void *stream)
+                        int out_dtype, uint64_t seed, uint32_t layer_id, int rht, void *ws, size_t ws_bytes, void *stream)
 {
     if (!dY || !Wq_ctx) return NVFP4_ERR_NULL;
     if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
@@ -535,7 +550,7 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
     const size_t gbytes = gemm_workspace_bytes(N, D, C, outer);
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
 
-    nvfp4_qcfg c3 = bwd_cfg(seed, layer_id, 3, outer), c4 = bwd_cfg(seed, layer_id, 4, outer);
+    nvfp4_qcfg c3 = bwd_cfg(seed, layer_id, 3, outer, rht), c4 = bwd_cfg(seed, layer_id, 4, outer, rht);
     QuantPlan p3{}, p4{};
     rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 0, &c3, &dYq, &p3);
     if (rc) return rc;
@@ -550,7 +565,7 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
 }
 
 int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C, void *dW,
-                        int out_dtype, uint64_t seed, uint32_t layer_id, void *ws, size_t ws_bytes, void *stream)
+                        int out_dtype, uint64_t seed, uint32_t layer_id, int rht, void *ws, size_t ws_bytes, void *stream)
 {
     if (!dY || !Xq_ctx) return NVFP4_ERR_NULL;
     if (N < 0 || D < 0 || C < 0) return NVFP4_ERR_SHAPE;
@@ -569,7 +584,7 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
     const size_t gbytes = gemm_workspace_bytes(C, D, N, outer);
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
 
-    nvfp4_qcfg c5 = bwd_cfg(seed, layer_id, 5, outer), c6 = bwd_cfg(seed, layer_id, 6, outer);
+    nvfp4_qcfg c5 = bwd_cfg(seed, layer_id, 5, outer, rht), c6 = bwd_cfg(seed, layer_id, 6, outer, rht);
     QuantPlan p5{}, p6{};
     rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 1, &c5, &dYq, &p5);
     if (rc) return rc;
@@ -584,7 +599,7 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
 }
 
 int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D,
-                     int64_t C, void *dX, void *dW, int out_dtype, uint64_t seed, uint32_t layer_id, void *ws,
+                     int64_t C, void *dX, void *dW, int out_dtype, uint64_t seed, uint32_t layer_id, int rht, void *ws,
                      size_t ws_bytes, void *stream)
 {
     if (!dY || !Xq_ctx || !Wq_ctx) return NVFP4_ERR_NULL;
@@ -613,7 +628,7 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
     void *gws = gbytes ? cv.take(gbytes) : nullptr;
 
     nvfp4_qcfg c[4];
-    for (int k = 0; k < 4; ++k) c[k] = bwd_cfg(seed, layer_id, 3 + k, outer);
+    for (int k = 0; k < 4; ++k) c[k] = bwd_cfg(seed, layer_id, 3 + k, outer, rht);
     if (outer == NVFP4_OUTER_TENSOR) {
         c[0].amax_in = amax;     // Q3 and Q5 share the maximum of dY
         c[2].amax_in = amax;

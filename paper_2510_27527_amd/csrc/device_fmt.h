@@ -141,6 +141,30 @@ __device__ __forceinline__ uint32_t quad_bits(uint32_t p, uint32_t k0, uint32_t 
     return h;
 }
 
+// ---- random Hadamard transform (Sec. 4.1, block 16) ------------------------------------------
+
+// x <- x H_16 (Sylvester order, entries +-1/4) on 16 values held by one lane: the four butterfly stages with strides
+// 1, 2, 4, 8 in that order, one rounding per addition, then the (exact) factor 1/4
+__device__ __forceinline__ void fwht16(float (&v)[16])
+{
+#pragma unroll
+    for (int h = 1; h < 16; h <<= 1)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (!(i & h)) {
+                const float a = v[i], c = v[i + h];
+                v[i] = a + c;
+                v[i + h] = a - c;
+            }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = v[i] * 0.25f;
+}
+
+// Bit of a sign word that decides position k (k mod 32 = e) along the grouped axis: every bit serves one position.
+// With this numbering the two bf16 of dword j of an aligned 8-run starting at e0 flip under
+// rotate_right(word, e0 / 2 + j) & 0x80008000.
+__device__ __forceinline__ constexpr int rht_sign_bit(int e) { return (15 + (e >> 1) + 16 * (e & 1)) & 31; }
+
 // ---- outer scale (Sec. 2.2, S_global) ---------------------------------------------------------
 
 struct OuterScale {

@@ -20,6 +20,8 @@ struct QuantParams {
     int scale_up;      // 0 nearest-even, 1 upward
     int outer;         // 0 tensor, 1 block128
     uint32_t k0, k1;   // stream key words
+    int rht;           // 1: random Hadamard transform (block 16) along the grouped axis first; 1 x 128 outer blocks only
+    uint32_t r0, r1;   // key words of the transform's sign stream
     // tensor maximum: either a device scalar, or `npart` partial maxima
     const float *amax_scalar;
     const float *amax_partials;

@@ -35,6 +35,7 @@ struct KArgs {
     const float *amax_partials;
     int npart;
     uint32_t k0, k1;
+    uint32_t r0, r1;      // random Hadamard transform: key words of the sign stream
 };
 
 // tensor maximum for this workgroup: a scalar, or the maximum of the partials
@@ -160,14 +161,20 @@ struct RowJob {
     const uint4 *src;
     int64_t nchunks;
     KArgs a;
+    uint32_t nblk;       // RHT: 128-element blocks per row (K / 128)
 };
 
 // first_second: first workgroup of the second job (0xFFFFFFFF when the launch has one job)
-template <int ROUND, bool SUP, int OUTER, bool DEQ>
+// RHT (1 x 128 outer blocks only): every group of 16 is first multiplied by S H_16 (Sec. 4.1).  The two lanes of a
+// group do the strides 1, 2, 4 on their own eight values and the stride 8 across the pair; the signs come from a
+// table of the 256 sign words (32 positions each) that the workgroup's 64 outer blocks can touch.
+template <int ROUND, bool SUP, int OUTER, bool DEQ, bool RHT = false>
 __global__ __launch_bounds__(kThreads) void quant_row_kernel(RowJob j0, RowJob j1, unsigned first_second)
 {
+    static_assert(!RHT || (OUTER == 1 && !DEQ), "the transform is provided with 1 x 128 outer blocks");
     __shared__ float inv_tab[128];
     __shared__ float red[4];
+    __shared__ uint32_t sign_tab[RHT ? kThreads : 1];
     const int tid = threadIdx.x;
     const bool second = blockIdx.x >= first_second;
     const uint4 *__restrict__ src = second ? j1.src : j0.src;
@@ -184,6 +191,12 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(RowJob j0, RowJob j
         if (full || c0 + it * kThreads < nchunks) vs[it] = ld_stream(src + c0 + it * kThreads);
     }
     fill_inv_table(inv_tab);
+    if (RHT) {
+        // entry t: sign word (t & 3) of the (t >> 2)-th outer block this workgroup covers; blocks wrap at the end of a row
+        const uint32_t nblk = second ? j1.nblk : j0.nblk;
+        const uint32_t kb = (uint32_t)(((uint64_t)bid * (kRowIter * kThreads / 16) + (uint32_t)(tid >> 2)) % nblk);
+        sign_tab[tid] = quad_bits(kb * 4u + (uint32_t)(tid & 3), a.r0, a.r1);
+    }
     OuterScale os;
     // Largest dequantized magnitude.  In tensor mode the group holding the tensor maximum always gets
     // the scale 448 and its largest element the code 6, so the maximum is 6 * 448 * S_g in closed form;
@@ -207,24 +220,59 @@ __global__ __launch_bounds__(kThreads) void quant_row_kernel(RowJob j0, RowJob j
         for (int it = 0; it < kRowIter; ++it) {
             const int64_t c = c0 + it * kThreads;
             const bool valid = !CHECK || c < nchunks;
-            const uint4 v = vs[it];
-            const uint32_t hm = absmax8_bits(v);
-            const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
-            const uint32_t bm = hm > o1 ? hm : o1;
+            uint4 v = vs[it];
+            float x[8];
+            uint32_t bm;                                       // group maximum: bf16 pattern, or binary32 pattern with RHT
+            if constexpr (!RHT) {
+                const uint32_t hm = absmax8_bits(v);
+                const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
+                bm = hm > o1 ? hm : o1;
+                x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
+                x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
+            } else {
+                // signs: this chunk is run (tid & 3) of eight positions of its sign word
+                const uint32_t w = sign_tab[it * (kThreads / 4) + (tid >> 2)];
+                const int rot = 4 * (tid & 3);
+                v.x ^= __builtin_amdgcn_alignbit(w, w, rot) & 0x80008000u;
+                v.y ^= __builtin_amdgcn_alignbit(w, w, rot + 1) & 0x80008000u;
+                v.z ^= __builtin_amdgcn_alignbit(w, w, rot + 2) & 0x80008000u;
+                v.w ^= __builtin_amdgcn_alignbit(w, w, rot + 3) & 0x80008000u;
+                x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
+                x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
+#pragma unroll
+                for (int h = 1; h < 8; h <<= 1)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (!(i & h)) {
+                            const float p = x[i], q = x[i + h];
+                            x[i] = p + q;
+                            x[i + h] = p - q;
+                        }
+                // stride 8: the even lane of the pair holds positions 0..7 (sum), the odd lane 8..15 (difference)
+                const uint32_t flip = (uint32_t)(tid & 1) << 31;
+                uint32_t hm = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float other = u2f(dpp<DPP_QUAD_XOR1>(f2u(x[i])));
+                    x[i] = (other + u2f(f2u(x[i]) ^ flip)) * 0.25f;
+                    const uint32_t ab = f2u(x[i]) & 0x7FFFFFFFu;
+                    hm = hm > ab ? hm : ab;
+                }
+                const uint32_t o1 = dpp<DPP_QUAD_XOR1>(hm);
+                bm = hm > o1 ? hm : o1;
+            }
             if (OUTER == 1) {
                 uint32_t gm = bm, t;
                 t = dpp<DPP_QUAD_XOR2>(gm);       gm = gm > t ? gm : t;
                 t = dpp<DPP_ROW_HALF_MIRROR>(gm); gm = gm > t ? gm : t;
                 t = dpp<DPP_ROW_MIRROR>(gm);      gm = gm > t ? gm : t;
-                os = outer_scale(u2f(gm << 16));
+                os = outer_scale(RHT ? u2f(gm) : u2f(gm << 16));
                 if (valid && (tid & 15) == 0) a.gscale[c >> 4] = os.S_g;
             }
-            const float amax_b = u2f(bm << 16);
+            const float amax_b = RHT ? u2f(bm) : u2f(bm << 16);
             const float s = amax_b * os.inv_cg;
             const uint32_t sc = e4m3_round<SUP>(s);
             const float r = os.inv_sg * inv_tab[sc];
-            const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
-                                bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
             const uint32_t q = quant8<ROUND, SUP>(x, r, (uint32_t)(c * 2), a.k0, a.k1);
             if (valid) a.codes[c] = q;
             // four scale bytes (lanes c, c+2, c+4, c+6) travel to the lane with c % 8 == 0
@@ -431,9 +479,12 @@ __global__ __launch_bounds__(kThreads) void quant_dual_kernel(ColArgs a)
 // from cache) quantizes.
 constexpr int kStripC = 128, kStripR = 128, kSlabs = kStripR / 16;
 
-template <int ROUND, bool SUP, bool PACKED, int OUTER>
+// RHT (with OUTER = 1): a lane's 16 values of a column are one block of the random Hadamard transform (Sec. 4.1), all
+// in its own registers; the signs depend on the source row only, so they are wave-uniform masks.
+template <int ROUND, bool SUP, bool PACKED, int OUTER, bool RHT = false>
 __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArgs a1, unsigned first_second)
 {
+    static_assert(!RHT || OUTER == 1, "the transform is provided with 1 x 128 outer blocks");
     __shared__ float inv_tab[128];
     __shared__ float red[4];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -519,13 +570,20 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
     };
     // returns the two column maxima of the slab
     auto decode = [&](const Raw &r, int s, float (&x0)[16], float (&x1)[16], float &m0, float &m1) {
+        // RHT: the slab's 16 source rows are positions 16 (s & 1) .. + 15 of sign word (R0 + 16 s) / 32 (R0 is a multiple
+        // of 128); the word is the same for the whole wave
+        uint32_t sw = 0;
+        if (RHT) sw = __builtin_amdgcn_readfirstlane(quad_bits((uint32_t)((R0 + 16 * s) >> 5), a.k.r0, a.k.r1));
+        auto flips = [&](int i) { return ((sw >> rht_sign_bit(16 * (s & 1) + i)) & 1u) != 0; };   // uniform
         if constexpr (!PACKED) {
             ushort2_t m2 = {0, 0};
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                m2 = __builtin_elementwise_max(m2, as_us2(r.w[i] & 0x7FFF7FFFu));
-                x0[i] = bf16_lo(r.w[i]);
-                x1[i] = bf16_hi(r.w[i]);
+                uint32_t w = r.w[i];
+                if (RHT) w ^= flips(i) ? 0x80008000u : 0u;
+                m2 = __builtin_elementwise_max(m2, as_us2(w & 0x7FFF7FFFu));
+                x0[i] = bf16_lo(w);
+                x1[i] = bf16_hi(w);
             }
             m0 = u2f((uint32_t)m2.x << 16);
             m1 = u2f((uint32_t)m2.y << 16);
@@ -534,9 +592,21 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const float sg = src_blocks ? row_sg[16 * s + i] : src_sg_tensor;
-                const float2_t pv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r.w[i], 1.0f, 0) * e4m3_value(r.sb[i]);   // exact
+                uint32_t cb = r.w[i];
+                if (RHT) cb ^= flips(i) ? 0x88u : 0u;               // the sign bits of the two codes
+                const float2_t pv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cb, 1.0f, 0) * e4m3_value(r.sb[i]);   // exact
                 x0[i] = pv.x * sg;                                  // the binary32 dequantized value: one rounding
                 x1[i] = pv.y * sg;
+                m0 = fmaxf(m0, fabsf(x0[i]));
+                m1 = fmaxf(m1, fabsf(x1[i]));
+            }
+        }
+        if (RHT) {
+            fwht16(x0);
+            fwht16(x1);
+            m0 = m1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
                 m0 = fmaxf(m0, fabsf(x0[i]));
                 m1 = fmaxf(m1, fabsf(x1[i]));
             }
@@ -552,7 +622,7 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
         for (int s = 0; s < kSlabs; ++s) {
             if (s >= nslab) break;
             if (s + 1 < nslab) fetch(std::false_type{}, s + 1, nxt);
-            if constexpr (!PACKED) {
+            if constexpr (!PACKED && !RHT) {
                 ushort2_t m2 = {0, 0};
 #pragma unroll
                 for (int i = 0; i < 16; ++i) m2 = __builtin_elementwise_max(m2, as_us2(cur.w[i] & 0x7FFF7FFFu));
@@ -676,15 +746,24 @@ KArgs make_kargs(const QuantParams &p, const QuantOut &o)
     k.npart = p.npart;
     k.k0 = p.k0;
     k.k1 = p.k1;
+    k.r0 = p.r0;
+    k.r1 = p.r1;
     return k;
 }
 
 template <int ROUND, bool SUP, int OUTER>
-void launch_row_t(const RowJob &j0, const RowJob &j1, bool deq, hipStream_t st)
+void launch_row_t(const RowJob &j0, const RowJob &j1, bool deq, bool rht, hipStream_t st)
 {
     const int64_t per_wg = (int64_t)kThreads * kRowIter;
     const unsigned g0 = (unsigned)((j0.nchunks + per_wg - 1) / per_wg), g1 = (unsigned)((j1.nchunks + per_wg - 1) / per_wg);
     const unsigned first_second = g1 ? g0 : 0xFFFFFFFFu;
+    if constexpr (OUTER == 1) {
+        if (rht) {
+            hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, 1, false, true>), dim3(g0 + g1), dim3(kThreads), 0, st, j0, j1,
+                               first_second);
+            return;
+        }
+    }
     if (deq)
         hipLaunchKernelGGL((quant_row_kernel<ROUND, SUP, OUTER, true>), dim3(g0 + g1), dim3(kThreads), 0, st, j0, j1,
                            first_second);
@@ -693,26 +772,27 @@ void launch_row_t(const RowJob &j0, const RowJob &j1, bool deq, hipStream_t st)
                            first_second);
 }
 
-template <bool PACKED, int OUTER>
+template <bool PACKED, int OUTER, bool RHT>
 void launch_colw_t(const ColArgs &a0, const ColArgs &a1, bool pair, int rounding, int scale_up, hipStream_t st)
 {
     const unsigned g0 = colw_grid(a0), g1 = pair ? colw_grid(a1) : 0;
     const unsigned first_second = pair ? g0 : 0xFFFFFFFFu;
     const dim3 grid(g0 + g1);
     if (rounding == 0) {
-        if (scale_up) hipLaunchKernelGGL((quant_colw_kernel<0, true, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
-        else          hipLaunchKernelGGL((quant_colw_kernel<0, false, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        if (scale_up) hipLaunchKernelGGL((quant_colw_kernel<0, true, PACKED, OUTER, RHT>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        else          hipLaunchKernelGGL((quant_colw_kernel<0, false, PACKED, OUTER, RHT>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
     } else {
-        if (scale_up) hipLaunchKernelGGL((quant_colw_kernel<1, true, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
-        else          hipLaunchKernelGGL((quant_colw_kernel<1, false, PACKED, OUTER>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        if (scale_up) hipLaunchKernelGGL((quant_colw_kernel<1, true, PACKED, OUTER, RHT>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
+        else          hipLaunchKernelGGL((quant_colw_kernel<1, false, PACKED, OUTER, RHT>), grid, dim3(kThreads), 0, st, a0, a1, first_second);
     }
 }
 
 template <bool PACKED>
 void launch_colw(const ColArgs &a0, const ColArgs &a1, bool pair, const QuantParams &p, hipStream_t st)
 {
-    if (p.outer == 0) launch_colw_t<PACKED, 0>(a0, a1, pair, p.rounding, p.scale_up, st);
-    else launch_colw_t<PACKED, 1>(a0, a1, pair, p.rounding, p.scale_up, st);
+    if (p.outer == 0) launch_colw_t<PACKED, 0, false>(a0, a1, pair, p.rounding, p.scale_up, st);
+    else if (!p.rht) launch_colw_t<PACKED, 1, false>(a0, a1, pair, p.rounding, p.scale_up, st);
+    else launch_colw_t<PACKED, 1, true>(a0, a1, pair, p.rounding, p.scale_up, st);
 }
 
 }  // namespace
@@ -755,15 +835,16 @@ void launch_zero_scalar(float *p, hipStream_t st)
 static void launch_row_sel(const RowJob &j0, const RowJob &j1, const QuantParams &p, bool deq, hipStream_t st)
 {
     const int sel = (p.rounding << 2) | (p.scale_up << 1) | p.outer;
+    const bool rht = p.rht != 0;
     switch (sel) {
-        case 0: launch_row_t<0, false, 0>(j0, j1, deq, st); break;
-        case 1: launch_row_t<0, false, 1>(j0, j1, deq, st); break;
-        case 2: launch_row_t<0, true, 0>(j0, j1, deq, st); break;
-        case 3: launch_row_t<0, true, 1>(j0, j1, deq, st); break;
-        case 4: launch_row_t<1, false, 0>(j0, j1, false, st); break;
-        case 5: launch_row_t<1, false, 1>(j0, j1, false, st); break;
-        case 6: launch_row_t<1, true, 0>(j0, j1, false, st); break;
-        default: launch_row_t<1, true, 1>(j0, j1, false, st); break;
+        case 0: launch_row_t<0, false, 0>(j0, j1, deq, rht, st); break;
+        case 1: launch_row_t<0, false, 1>(j0, j1, deq, rht, st); break;
+        case 2: launch_row_t<0, true, 0>(j0, j1, deq, rht, st); break;
+        case 3: launch_row_t<0, true, 1>(j0, j1, deq, rht, st); break;
+        case 4: launch_row_t<1, false, 0>(j0, j1, false, rht, st); break;
+        case 5: launch_row_t<1, false, 1>(j0, j1, false, rht, st); break;
+        case 6: launch_row_t<1, true, 0>(j0, j1, false, rht, st); break;
+        default: launch_row_t<1, true, 1>(j0, j1, false, rht, st); break;
     }
 }
 
@@ -772,8 +853,8 @@ hipError_t launch_quant_row_bf16(const void *src, int64_t rows, int64_t K, const
 {
     const int64_t nchunks = rows * K / 8;
     if (nchunks == 0) return hipSuccess;
-    RowJob j0{reinterpret_cast<const uint4 *>(src), nchunks, make_kargs(p, o)}, j1{};
-    launch_row_sel(j0, j1, p, o.amax_deq != nullptr && p.rounding == 0, st);
+    RowJob j0{reinterpret_cast<const uint4 *>(src), nchunks, make_kargs(p, o), (uint32_t)(K / 128)}, j1{};
+    launch_row_sel(j0, j1, p, o.amax_deq != nullptr && p.rounding == 0 && !p.rht, st);
     return hipGetLastError();
 }
 
@@ -783,8 +864,8 @@ hipError_t launch_quant_row_bf16_pair(const void *src0, int64_t rows0, int64_t K
 {
     if (rows0 * K0 == 0) return launch_quant_row_bf16(src1, rows1, K1, p1, o1, st);
     if (rows1 * K1 == 0) return launch_quant_row_bf16(src0, rows0, K0, p0, o0, st);
-    RowJob j0{reinterpret_cast<const uint4 *>(src0), rows0 * K0 / 8, make_kargs(p0, o0)};
-    RowJob j1{reinterpret_cast<const uint4 *>(src1), rows1 * K1 / 8, make_kargs(p1, o1)};
+    RowJob j0{reinterpret_cast<const uint4 *>(src0), rows0 * K0 / 8, make_kargs(p0, o0), (uint32_t)(K0 / 128)};
+    RowJob j1{reinterpret_cast<const uint4 *>(src1), rows1 * K1 / 8, make_kargs(p1, o1), (uint32_t)(K1 / 128)};
     launch_row_sel(j0, j1, p0, (o0.amax_deq != nullptr || o1.amax_deq != nullptr) && p0.rounding == 0, st);
     return hipGetLastError();
 }

@@ -66,6 +66,8 @@ def test_quantize_rejects_bad_arguments(lib):
     assert _quant(lib, cfg=B.CQcfg(7, 0, 0, 0, 0, None)) == -3
     assert _quant(lib, cfg=B.CQcfg(0, 9, 0, 0, 0, None)) == -3
     assert _quant(lib, cfg=B.CQcfg(0, 0, 4, 0, 0, None)) == -3
+    assert _quant(lib, Cc=128, cfg=B.CQcfg(1, 0, 0, 0, 0, None, 1, 7)) == -3      # transform without 1 x 128 outer blocks
+    assert _quant(lib, Cc=128, cfg=B.CQcfg(1, 0, 1, 0, 0, None, 3, 7)) == -3
     assert _quant(lib, ws=None) == -4
     assert _quant(lib, ws_bytes=16) == -4
     assert _quant(lib, src=FAKE + 2) == -5
@@ -123,26 +125,30 @@ def test_gemm_and_linear_reject_bad_arguments(lib):
     assert fwd(128, 128, 64, wsb=8) == -4
     assert fwd(-1, 128, 64) == -2
     W = _tensor(64, 128)
-    dx = lambda N, D, Cc, w=W, wsb=1 << 40: lib.nvfp4_linear_bwd_dx(FAKE, C.byref(w), N, D, Cc, FAKE, 0, 0, 0, FAKE, wsb, None)
+    dx = lambda N, D, Cc, w=W, wsb=1 << 40, rht=0: lib.nvfp4_linear_bwd_dx(FAKE, C.byref(w), N, D, Cc, FAKE, 0, 0, 0, rht, FAKE, wsb, None)
     assert dx(128, 128, 32) == -2                          # C % 64
     assert dx(128, 256, 64) == -6
     assert dx(128, 128, 64, wsb=100) == -4
     X = _tensor(128, 128)
-    dw = lambda N, D, Cc, x=X, wsb=1 << 40: lib.nvfp4_linear_bwd_dw(FAKE, C.byref(x), N, D, Cc, FAKE, 0, 0, 0, FAKE, wsb, None)
+    dw = lambda N, D, Cc, x=X, wsb=1 << 40, rht=0: lib.nvfp4_linear_bwd_dw(FAKE, C.byref(x), N, D, Cc, FAKE, 0, 0, 0, rht, FAKE, wsb, None)
     assert dw(96, 128, 64) == -2                           # N % 64
     assert dw(128, 64, 64) == -6
     assert dw(128, 128, 64, wsb=100) == -4
+    # the random Hadamard transform comes with 1 x 128 outer blocks: tensor-mode contexts refuse it
+    assert dx(128, 128, 64, rht=1) == -3 and dw(128, 128, 64, rht=1) == -3
+    assert dx(128, 128, 128, w=_tensor(128, 128, outer=1), rht=2) == -3
 
 
 def test_fused_backward_rejects_bad_arguments(lib):
     X, W = _tensor(128, 128), _tensor(64, 128)
-    f = lambda N, D, Cc, x=X, w=W, wsb=1 << 40: lib.nvfp4_linear_bwd(FAKE, C.byref(x), C.byref(w), N, D, Cc, FAKE, FAKE, 0,
-                                                                  0, 0, FAKE, wsb, None)
+    f = lambda N, D, Cc, x=X, w=W, wsb=1 << 40, rht=0: lib.nvfp4_linear_bwd(FAKE, C.byref(x), C.byref(w), N, D, Cc, FAKE, FAKE,
+                                                                         0, 0, 0, rht, FAKE, wsb, None)
     assert f(128, 128, 32) == -2
     assert f(96, 128, 64) == -2
     assert f(128, 64, 64) == -6
     assert f(128, 128, 64, wsb=64) == -4
-    assert lib.nvfp4_linear_bwd(None, C.byref(X), C.byref(W), 128, 128, 64, FAKE, FAKE, 0, 0, 0, FAKE, 1 << 40, None) == -1
+    assert lib.nvfp4_linear_bwd(None, C.byref(X), C.byref(W), 128, 128, 64, FAKE, FAKE, 0, 0, 0, 0, FAKE, 1 << 40, None) == -1
+    assert f(128, 128, 64, rht=1) == -3
     assert lib.nvfp4_workspace_bytes(B.OP_LINEAR_BWD, 128, 128, 64, 0) >= \
         lib.nvfp4_workspace_bytes(B.OP_LINEAR_BWD_DX, 128, 128, 64, 0)
 

@@ -64,9 +64,10 @@ def product_ok(got_rows: torch.Tensor, ref, absref, what):
     assert np.all(err <= tol), "%s: err %.3e tol %.3e at %s" % (what, err[worst], tol[worst], worst)
 
 
-def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0):
+def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0, rht=False):
     B = tj.binding
-    cfg = cfg + ("/block128" if outer else "")
+    cfg = cfg + ("/block128" if outer else "") + ("/rht" if rht else "")
+    rid = (lambda prod: li * 8 + (7 if prod == "dx" else 0)) if rht else (lambda prod: None)
     say("[%s %s] N=%d D=%d C=%d: inputs" % (cfg, name, N, D, C))
     Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed, kind)
     X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
@@ -76,7 +77,7 @@ def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0):
     dX = torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
     dW = torch.empty((C, D), dtype=torch.bfloat16, device="cuda")
     tj.linear_fwd(X, W, B.OUT_BF16, Y=Y, Xq=Xq, Wq=Wq, ws=ws, outer=outer)
-    tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_BF16, dX=dX, dW=dW, ws=ws)
+    tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_BF16, dX=dX, dW=dW, ws=ws, rht=rht)
     torch.cuda.synchronize()
 
     say("[%s %s] oracle forward operands" % (cfg, name))
@@ -84,14 +85,14 @@ def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0):
     same_bytes(Xq, oXq, "Q1(X)", check_amax=True)
     same_bytes(Wq, oWq, "Q2(W)", check_amax=True)
     say("[%s %s] oracle backward operands" % (cfg, name))
-    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, sr_seed, li, outer=outer)
-    same_bytes(tj.quantize(dY, 0, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 3, outer=outer), o3, "Q3(dY)")
-    same_bytes(tj.quantize(Wq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 4, outer=outer), o4, "Q4(W_hat)")
-    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, sr_seed, li, outer=outer)
-    same_bytes(tj.quantize(dY, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 5, outer=outer), o5, "Q5(dY^T)")
-    same_bytes(tj.quantize(Xq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 6, outer=outer), o6, "Q6(X_hat)")
-    dX1 = tj.linear_bwd_dx(dY, Wq, sr_seed, li, B.OUT_BF16)
-    dW1 = tj.linear_bwd_dw(dY, Xq, sr_seed, li, B.OUT_BF16)
+    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, sr_seed, li, outer=outer, rht=rht)
+    same_bytes(tj.quantize(dY, 0, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 3, outer=outer, rht_id=rid("dx")), o3, "Q3(dY)")
+    same_bytes(tj.quantize(Wq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 4, outer=outer, rht_id=rid("dx")), o4, "Q4(W_hat)")
+    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, sr_seed, li, outer=outer, rht=rht)
+    same_bytes(tj.quantize(dY, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 5, outer=outer, rht_id=rid("dw")), o5, "Q5(dY^T)")
+    same_bytes(tj.quantize(Xq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 6, outer=outer, rht_id=rid("dw")), o6, "Q6(X_hat)")
+    dX1 = tj.linear_bwd_dx(dY, Wq, sr_seed, li, B.OUT_BF16, rht=rht)
+    dW1 = tj.linear_bwd_dw(dY, Xq, sr_seed, li, B.OUT_BF16, rht=rht)
     torch.cuda.synchronize()
     assert torch.equal(dX, dX1) and torch.equal(dW, dW1), "fused backward differs from the separate calls"
 
@@ -102,7 +103,7 @@ def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0):
         say("[%s %s] FP32-output run" % (cfg, name))
         del dX1, dW1
         Y32, _, _ = tj.linear_fwd(X, W, B.OUT_F32, Xq=Xq, Wq=Wq, ws=ws, outer=outer)
-        dX32, dW32 = tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_F32, ws=ws)
+        dX32, dW32 = tj.linear_bwd(dY, Xq, Wq, sr_seed, li, B.OUT_F32, ws=ws, rht=rht)
         torch.cuda.synchronize()
         outs32 = {"Y": Y32, "dX": dX32, "dW": dW32}
     rng = np.random.default_rng(seed)
@@ -133,6 +134,14 @@ def test_full_size_linear_block128(cfg, li):
     """the same workloads with the paper's 1 x 128 outer blocks on every operand (no maximum pass anywhere)"""
     name, N, D, C, seed, kind = wl.config_linears(cfg)[li]
     run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed=0, outer=tj.binding.OUTER_BLOCK128)
+
+
+@pytest.mark.parametrize("cfg,li", [pytest.param(c, 0, id=c) for c in ("cfg1_single", "cfg2_block768", "cfg3_block1024", "cfg5_square8192")])
+def test_full_size_linear_block128_rht(cfg, li):
+    """the first linear of every workload as TetraJet-v2-base runs it: 1 x 128 outer blocks and the random Hadamard
+    transform on both operands of both backward products (Sec. 4.1)"""
+    name, N, D, C, seed, kind = wl.config_linears(cfg)[li]
+    run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed=0, outer=tj.binding.OUTER_BLOCK128, rht=True)
 
 
 def test_quantizer_stress_full():

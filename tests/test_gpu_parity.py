@@ -415,6 +415,67 @@ def test_linear_block128_mode(N, D, C):
     assert torch.equal(dX, dX2) and torch.equal(dW, dW2)
 
 
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_quantizers_with_random_hadamard_transform(rounding):
+    """Sec. 4.1: every quantizer that serves the backward pass, with x S H_16 along the grouped axis first (1 x 128
+    outer blocks): row-wise and column-wise from bf16 (Q3, Q5), column-wise from packed tensors (Q4, Q6); bytes."""
+    B = tj.binding
+    O, OB = oracle.OUTER_BLOCK128, B.OUTER_BLOCK128
+    for shape in [(128, 128), (260, 384), (1152, 1024), (40, 8320)]:
+        bits = wl.normal_bf16(shape, 1e-3, 480 + shape[0], 1e-2, 50.0)
+        bits[0, :128] = 0
+        x = dev_bf16(bits)
+        ref = oracle.quantize_bf16(bits, 0, rounding, outer=O, seed=3, tensor_id=11, rht_id=15)
+        assert_same(tj.quantize(x, 0, rounding, outer=OB, seed=3, tensor_id=11, rht_id=15), ref, "row rht %s" % (shape,))
+        # another sign stream gives other bytes
+        other = tj.quantize(x, 0, rounding, outer=OB, seed=3, tensor_id=11, rht_id=16)
+        torch.cuda.synchronize()
+        assert not np.array_equal(other.codes.cpu().numpy(), ref.codes)
+    for shape in [(128, 8), (256, 512), (1152, 136), (2048, 1040)]:
+        bits = wl.student_t_bf16(shape, 3.0, 0.1, 490 + shape[1])
+        ref = oracle.quantize_bf16(bits, 1, rounding, outer=O, seed=4, tensor_id=13, rht_id=8)
+        assert_same(tj.quantize(dev_bf16(bits), 1, rounding, outer=OB, seed=4, tensor_id=13, rht_id=8), ref, "col rht %s" % (shape,))
+    for shape in [(128, 128), (384, 1152), (1024, 256)]:
+        for src_outer in (1, 0):
+            bits = wl.normal_bf16(shape, 1.0, 500 + shape[0], 1e-2, 50.0)
+            src_ref = oracle.quantize_bf16(bits, 0, 0, outer=src_outer)
+            ref = oracle.requantize(src_ref, 1, rounding, outer=O, seed=17, tensor_id=6, rht_id=7)
+            got = tj.quantize(to_dev(src_ref), 1, rounding, outer=OB, seed=17, tensor_id=6, rht_id=7)
+            assert_same(got, ref, "requant rht %s src%d" % (shape, src_outer))
+
+
+@pytest.mark.parametrize("N,D,C", [(256, 512, 384), (1152, 256, 128)])
+def test_linear_backward_with_random_hadamard_transform(N, D, C):
+    """The backward pass of TetraJet-v2-base: 1 x 128 outer blocks, stochastic rounding, and the random Hadamard
+    transform on both operands of dX and of dW (Sec. 4.1); separate calls, the fused call, against the oracle."""
+    B = tj.binding
+    O = oracle.OUTER_BLOCK128
+    Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed=60 + N)
+    X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
+    Y, Xq, Wq = tj.linear_fwd(X, W, B.OUT_F32, outer=B.OUTER_BLOCK128)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb, outer=O)
+    o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, 5, 2, outer=O, rht=True)
+    o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, 5, 2, outer=O, rht=True)
+    dX = tj.linear_bwd_dx(dY, Wq, 5, 2, B.OUT_F32, rht=True)
+    dW = tj.linear_bwd_dw(dY, Xq, 5, 2, B.OUT_F32, rht=True)
+    check_product(dX, *oracle.gemm_nt(o3, o4), "dX rht")
+    check_product(dW, *oracle.gemm_nt(o5, o6), "dW rht")
+    dX2, dW2 = tj.linear_bwd(dY, Xq, Wq, 5, 2, B.OUT_F32, rht=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dX, dX2) and torch.equal(dW, dW2)
+    # and it is a different estimate from the one without the transform, of the same quantity
+    dX0 = tj.linear_bwd_dx(dY, Wq, 5, 2, B.OUT_F32)
+    torch.cuda.synchronize()
+    assert not torch.equal(dX, dX0)
+    exact = wl.bf16_to_f32(dYb).astype(np.float64) @ oracle.dequant_f64(oWq)
+    for est in (dX, dX0):
+        rel = np.abs(est.double().cpu().numpy() - exact).mean() / np.abs(exact).mean()
+        assert rel < 0.25
+    with pytest.raises(tj.NVFP4Error):
+        Yt, Xqt, Wqt = tj.linear_fwd(X, W, B.OUT_F32)
+        tj.linear_bwd_dx(dY, Wqt, 5, 2, B.OUT_F32, rht=True)       # per-tensor contexts: not provided
+
+
 def test_gemm_exact_on_integer_operands():
     """Scales 1 and grid-valued operands: the product is a small-integer matrix product, exact in FP32."""
     rng = np.random.default_rng(7)
