@@ -73,6 +73,12 @@ def lib():
         L.oracle_rht_sign.argtypes = [u64, u64]
         L.oracle_rht16_rows.restype = i32
         L.oracle_rht16_rows.argtypes = [p, i64, i64, u64]
+        L.oracle_quant_dequant_weight.restype = i32
+        L.oracle_quant_dequant_weight.argtypes = [p, i64, i64, p]
+        L.oracle_osci_update.restype = i32
+        L.oracle_osci_update.argtypes = [p, p, p, p, i64, i64, i32]
+        L.oracle_osci_suppress.restype = i64
+        L.oracle_osci_suppress.argtypes = [p, p, p, f32, i64, i64]
         L.oracle_dequant_f32.restype = i32
         L.oracle_dequant_f32.argtypes = [p, p, p, i64, i64, i32, p]
         L.oracle_dequant_f64.restype = i32
@@ -258,3 +264,33 @@ def linear_bwd_dw_operands(dY_bits, Xq: NVFP4, seed: int, layer_id: int, outer: 
     dYq = quantize_bf16(dY_bits, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 5), rht_id=rid)
     Xq2 = requantize(Xq, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 6), rht_id=rid)
     return dYq, Xq2
+
+
+# ----- OsciReset (Sec. 3.2-3.3; Alg. 1 and Appendix Alg. 2) ---------------------------------
+
+def quant_dequant_weight(W: np.ndarray) -> np.ndarray:
+    """Q(W): a binary32 [C, D] weight through the forward weight quantizer (groups along D, nearest, 1 x 128 outer
+    blocks) and back to binary32."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    out = np.empty_like(W)
+    if lib().oracle_quant_dequant_weight(_ptr(W), W.shape[0], W.shape[1], _ptr(out)) != 0:
+        raise ValueError("oracle_quant_dequant_weight: bad shape")
+    return out
+
+
+def osci_update(W, W_prev, dist_m, dist_q, t0: int):
+    """Appendix Alg. 2, in place on W_prev, dist_m, dist_q (float32, C-contiguous [C, D])."""
+    for a in (W, W_prev, dist_m, dist_q):
+        assert a.dtype == np.float32 and a.flags.c_contiguous and a.shape == W.shape
+    if lib().oracle_osci_update(_ptr(W), _ptr(W_prev), _ptr(dist_m), _ptr(dist_q), W.shape[0], W.shape[1], t0) != 0:
+        raise ValueError("oracle_osci_update: bad shape")
+
+
+def osci_suppress(W, dist_m, dist_q, tau: float) -> int:
+    """Alg. 1, in place on W; returns the number of elements reset."""
+    for a in (W, dist_m, dist_q):
+        assert a.dtype == np.float32 and a.flags.c_contiguous and a.shape == W.shape
+    n = lib().oracle_osci_suppress(_ptr(W), _ptr(dist_m), _ptr(dist_q), tau, W.shape[0], W.shape[1])
+    if n < 0:
+        raise ValueError("oracle_osci_suppress: bad shape")
+    return int(n)

@@ -61,6 +61,14 @@
  *       four butterfly stages with strides 1, 2, 4, 8 in that order, one
  *       rounding per addition, then one multiplication by 1/4 (exact).
  *
+ *   R13 OsciReset (Sec. 3.2-3.3, Alg. 1; Appendix Alg. 2): the master weights are
+ *       binary32; Q(W) is the forward weight quantizer Q2 applied to them - groups
+ *       along the input dimension, round-to-nearest, nearest-even scales, 1 x 128
+ *       outer blocks - followed by the binary32 dequantization of R8.  Distances
+ *       accumulate in binary32, one rounding per operation; the risk is the
+ *       binary32 quotient dist_Q / dist_M (0 / 0 compares false: an element that
+ *       never moved is not reset).
+ *
  * Parity status: R1, R6, R7, R12 (which bits, which summation order) are not fixed by the paper ("parity unpinned" by
  * the paper itself); they are pinned by the property tests in tests/ (grid
  * membership, exact round trips, scale/absmax invariants, closed-form SR
@@ -405,6 +413,64 @@ int oracle_dequant_f64(const uint8_t *codes, const uint8_t *scales, const float 
             out[r * K + k] = (double)code_value(nib) * S_b * S_g;
         }
     return 0;
+}
+
+/* -------------------------------------------------------------- OsciReset -- */
+
+/* Q(W) of R13: quantize-dequantize a binary32 [rows][K] matrix the way the forward pass quantizes a weight */
+int oracle_quant_dequant_weight(const float *W, int64_t rows, int64_t K, float *out)
+{
+    if (rows < 0 || K < 0 || K % 128) return -1;
+    uint8_t *codes = (uint8_t *)calloc((size_t)(rows * K / 2) + 1, 1);
+    uint8_t *scales = (uint8_t *)calloc((size_t)(rows * K / 16) + 1, 1);
+    float *gs = (float *)calloc((size_t)(rows * (K / 128)) + 1, sizeof(float));
+    int rc = quantize_rows_impl(W, rows, K, ROUND_RTN, SCALE_NE, OUTER_BLOCK128, 0, 0, codes, scales, gs, NULL, NULL, 0, NULL);
+    if (rc == 0) rc = oracle_dequant_f32(codes, scales, gs, rows, K, OUTER_BLOCK128, out);
+    free(codes); free(scales); free(gs);
+    return rc;
+}
+
+/* Appendix Alg. 2 (UpdateOscillationStats) for one weight matrix.  t0 = 0 opens a period: the distances are cleared
+ * and the snapshot W' is taken.  Otherwise dist_M += |W - W'|, dist_Q += |Q(W) - Q(W')|, then W' <- W. */
+int oracle_osci_update(const float *W, float *W_prev, float *dist_m, float *dist_q, int64_t rows, int64_t K, int t0)
+{
+    if (rows < 0 || K < 0 || K % 128 || t0 < 0) return -1;
+    const int64_t n = rows * K;
+    if (t0 == 0) {
+        for (int64_t i = 0; i < n; ++i) { dist_m[i] = 0.0f; dist_q[i] = 0.0f; W_prev[i] = W[i]; }
+        return 0;
+    }
+    float *q = (float *)malloc(sizeof(float) * (size_t)(n + 1)), *qp = (float *)malloc(sizeof(float) * (size_t)(n + 1));
+    int rc = oracle_quant_dequant_weight(W, rows, K, q);
+    if (rc == 0) rc = oracle_quant_dequant_weight(W_prev, rows, K, qp);
+    if (rc == 0)
+        for (int64_t i = 0; i < n; ++i) {
+            volatile float dm = fabsf(W[i] - W_prev[i]);
+            volatile float dq = fabsf(q[i] - qp[i]);
+            volatile float am = dist_m[i] + dm, aq = dist_q[i] + dq;
+            dist_m[i] = am;
+            dist_q[i] = aq;
+            W_prev[i] = W[i];
+        }
+    free(q); free(qp);
+    return rc;
+}
+
+/* Alg. 1 (OscillationSuppress) for one weight matrix: every element whose risk dist_Q / dist_M reaches tau is reset to
+ * the centre of its quantization bin, w <- w_FP4 * scale = Q(W) at that element.  Returns the number of resets (< 0: error). */
+int64_t oracle_osci_suppress(float *W, const float *dist_m, const float *dist_q, float tau, int64_t rows, int64_t K)
+{
+    if (rows < 0 || K < 0 || K % 128) return -1;
+    const int64_t n = rows * K;
+    float *q = (float *)malloc(sizeof(float) * (size_t)(n + 1));
+    int64_t count = 0;
+    if (oracle_quant_dequant_weight(W, rows, K, q) != 0) { free(q); return -1; }
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float risk = dist_q[i] / dist_m[i];
+        if (risk >= tau) { W[i] = q[i]; ++count; }
+    }
+    free(q);
+    return count;
 }
 
 /* ------------------------------------------------------------------ GEMM -- */
