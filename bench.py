@@ -300,6 +300,35 @@ def quantizer_lines(tj, wl, np, torch, dev, warm=300, reps=200):
     return res
 
 
+def osci_lines(tj, torch, dev):
+    """OsciReset kernels on an 8192 x 8192 binary32 weight (1 GiB of state: larger than the last-level cache):
+    statistics step 28 B per weight (W, W', dist_M, dist_Q read; W', dist_M, dist_Q written), reset up to 16 B per weight."""
+    n = 8192
+    gen = torch.Generator(device=dev).manual_seed(1)
+    W = torch.randn((n, n), device=dev, generator=gen) * 0.02
+    Wp, dm, dq = torch.empty_like(W), torch.empty_like(W), torch.empty_like(W)
+    tj.osci_update(W, Wp, dm, dq, 0)
+    W2 = W + torch.randn((n, n), device=dev, generator=gen) * 1e-4
+    res = {}
+    fn = lambda i: tj.osci_update(W2 if i % 2 == 0 else W, Wp, dm, dq, 1 + i)
+    for i in range(20):
+        fn(i)
+    torch.cuda.synchronize()
+    ms = time_events(torch, fn, 40)
+    gbs = 28.0 * n * n / (ms * 1e-3) / 1e9
+    res["osci_update_8192x8192"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    cnt = torch.zeros(1, dtype=torch.int64, device=dev)
+    fn = lambda i: tj.osci_suppress(W, dm, dq, 8.0, cnt)
+    for i in range(10):
+        fn(i)
+    torch.cuda.synchronize()
+    ms = time_events(torch, fn, 40)
+    gbs = 16.0 * n * n / (ms * 1e-3) / 1e9         # reads of W, dist_M, dist_Q, and (worst case, as here: nearly every
+                                                    # weight is over the threshold) W written back
+    res["osci_suppress_8192x8192"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    return res
+
+
 def extras(tj, wl, np, torch, dev, headline, outer):
     """Side measurements named by the metric: the steps of the other workloads, the quantizer GB/s on the 8192 x 8192
     stress tensor and the square 8192^3 product alone."""
@@ -316,6 +345,8 @@ def extras(tj, wl, np, torch, dev, headline, outer):
                                "frac_of_roofline_lower_bound": round(w.t_min * 1e3 / ms, 4)}
         del w
     res.update(quantizer_lines(tj, wl, np, torch, dev))
+
+    res.update(osci_lines(tj, torch, dev))
 
     # the square product alone, on pre-quantized operands: M = N = K = 8192
     n = 8192

@@ -200,6 +200,24 @@ int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_ten
                      uint64_t seed, uint32_t layer_id, int rht, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * OsciReset (Sec. 3.2-3.3) for one weight matrix of binary32 master weights W [C x D], all arrays device memory of
+ * C * D floats, 16-byte aligned, D % 128 == 0.  Q(W) below is the forward weight quantizer (groups of 16 along D,
+ * round-to-nearest, 1 x 128 outer blocks) followed by dequantization to binary32.
+ *
+ * nvfp4_osci_update - Appendix Alg. 2 (UpdateOscillationStats), one step of a tracking period.  t0 == 0 opens the
+ *   period: dist_m = dist_q = 0 and the snapshot W_prev = W.  t0 > 0: dist_m += |W - W_prev|,
+ *   dist_q += |Q(W) - Q(W_prev)|, then W_prev = W.  One pass, 28 bytes of traffic per weight.
+ * nvfp4_osci_suppress - Alg. 1 (OscillationSuppress): every element whose risk dist_q / dist_m reaches tau (the paper
+ *   uses 8) is reset to the centre of its quantization bin, W = Q(W) there; elements that never moved (0 / 0) are kept.
+ *   n_reset (device, optional, 8-byte aligned) is increased by the number of elements reset; the caller clears it.
+ * Errors: NULL, SHAPE, ENUM (t0 < 0, tau <= 0), ALIGN.
+ */
+int nvfp4_osci_update(const float *W, float *W_prev, float *dist_m, float *dist_q, int64_t C, int64_t D, int t0,
+                      void *stream);
+int nvfp4_osci_suppress(float *W, const float *dist_m, const float *dist_q, float tau, int64_t C, int64_t D,
+                        unsigned long long *n_reset, void *stream);
+
+/*
  * Scratch bytes an operation needs.  op = NVFP4_OP_*.  QUANTIZE: (N, D) = (R, C) of the source, C ignored.
  * GEMM: Out is [N x C] with reduction length D.  LINEAR_*: as in the calls above.  Returns 0 for a bad op.
  */

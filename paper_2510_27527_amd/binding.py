@@ -24,7 +24,7 @@ SRC_BF16, SRC_NVFP4 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW, OP_LINEAR_BWD = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_gemm_nt_static", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd",
+EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_gemm_nt_static", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd", "nvfp4_osci_update", "nvfp4_osci_suppress",
            "nvfp4_workspace_bytes", "nvfp4_gemm_plan", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
 
 
@@ -75,6 +75,10 @@ def lib():
         L.nvfp4_linear_bwd.restype = i32
         L.nvfp4_linear_bwd.argtypes = [vp, C.POINTER(CTensor), C.POINTER(CTensor), i64, i64, i64, vp, vp, i32, u64, u32,
                                        i32, vp, sz, vp]
+        L.nvfp4_osci_update.restype = i32
+        L.nvfp4_osci_update.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
+        L.nvfp4_osci_suppress.restype = i32
+        L.nvfp4_osci_suppress.argtypes = [vp, vp, vp, C.c_float, i64, i64, vp, vp]
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
         L.nvfp4_gemm_plan.restype = i32
@@ -329,3 +333,28 @@ def linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, la
                                 layer_id, int(rht), _ptr(ws), ws.numel(), _stream())
     _check(rc, "nvfp4_linear_bwd")
     return dX, dW
+
+
+def _check_f32(t: torch.Tensor, shape, what: str):
+    assert t.dtype == torch.float32 and tuple(t.shape) == tuple(shape) and t.is_contiguous() and t.is_cuda, what
+
+
+def osci_update(W: torch.Tensor, W_prev: torch.Tensor, dist_m: torch.Tensor, dist_q: torch.Tensor, t0: int):
+    """nvfp4_osci_update: one step of the oscillation statistics of a float32 [C, D] weight, in place."""
+    Cc, D = W.shape
+    for t, n in ((W, "W"), (W_prev, "W_prev"), (dist_m, "dist_m"), (dist_q, "dist_q")):
+        _check_f32(t, (Cc, D), n)
+    _check(lib().nvfp4_osci_update(_ptr(W), _ptr(W_prev), _ptr(dist_m), _ptr(dist_q), Cc, D, t0, _stream()), "nvfp4_osci_update")
+
+
+def osci_suppress(W: torch.Tensor, dist_m: torch.Tensor, dist_q: torch.Tensor, tau: float,
+                  n_reset: Optional[torch.Tensor] = None):
+    """nvfp4_osci_suppress: reset the oscillating elements of W in place; n_reset (int64 [1], optional) accumulates
+    their number."""
+    Cc, D = W.shape
+    for t, n in ((W, "W"), (dist_m, "dist_m"), (dist_q, "dist_q")):
+        _check_f32(t, (Cc, D), n)
+    if n_reset is not None:
+        assert n_reset.dtype == torch.int64 and n_reset.numel() == 1 and n_reset.is_cuda
+    _check(lib().nvfp4_osci_suppress(_ptr(W), _ptr(dist_m), _ptr(dist_q), tau, Cc, D, _ptr(n_reset), _stream()),
+           "nvfp4_osci_suppress")

@@ -485,6 +485,37 @@ int nvfp4_gemm_nt_static(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out
     return run_gemm(A, B, Out, out_dtype, ws, need, static_cast<hipStream_t>(stream));
 }
 
+static int check_osci(const void *W, const void *a, const void *b, int64_t C, int64_t D)
+{
+    if (!W || !a || !b) return NVFP4_ERR_NULL;
+    if (C < 0 || D < 0 || D % 128 != 0) return NVFP4_ERR_SHAPE;
+    if (C > 0 && D > kMaxElems / C) return NVFP4_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(a) || !aligned16(b)) return NVFP4_ERR_ALIGN;
+    return NVFP4_OK;
+}
+
+int nvfp4_osci_update(const float *W, float *W_prev, float *dist_m, float *dist_q, int64_t C, int64_t D, int t0, void *stream)
+{
+    int rc = check_osci(W, W_prev, dist_m, C, D);
+    if (rc) return rc;
+    if (!dist_q) return NVFP4_ERR_NULL;
+    if (!aligned16(dist_q)) return NVFP4_ERR_ALIGN;
+    if (t0 < 0) return NVFP4_ERR_ENUM;
+    return launch_osci_update(W, W_prev, dist_m, dist_q, C * D, t0 == 0, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_osci_suppress(float *W, const float *dist_m, const float *dist_q, float tau, int64_t C, int64_t D,
+                        unsigned long long *n_reset, void *stream)
+{
+    const int rc = check_osci(W, dist_m, dist_q, C, D);
+    if (rc) return rc;
+    if (!(tau > 0.0f)) return NVFP4_ERR_ENUM;
+    if (n_reset && (reinterpret_cast<uintptr_t>(n_reset) & 7u)) return NVFP4_ERR_ALIGN;
+    return launch_osci_suppress(W, dist_m, dist_q, tau, C * D, n_reset, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
 int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t C, void *Y, int out_dtype,
                      nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx, int outer_mode, void *ws, size_t ws_bytes,
                      void *stream)

@@ -66,6 +66,16 @@ __device__ __forceinline__ uint32_t e4m3_round_up(float s)
     return s < 0x1p-6f ? cs : (uint32_t)cn;
 }
 
+// reciprocals of all E4M3 values into a 128-entry table (entry 0 = 0, so a zero scale gives all-zero codes); the first
+// 128 threads of the workgroup write it, a barrier must follow
+__device__ __forceinline__ void fill_inv_table(float *tab)
+{
+    if (threadIdx.x < 128) {
+        float v = e4m3_value(threadIdx.x);
+        tab[threadIdx.x] = (threadIdx.x == 0 || threadIdx.x == 127) ? 0.0f : 1.0f / v;
+    }
+}
+
 template <bool UP>
 __device__ __forceinline__ uint32_t e4m3_round(float s) { return UP ? e4m3_round_up(s) : e4m3_round_ne(s); }
 

@@ -86,6 +86,11 @@ void gemm_plan(int64_t M, int64_t N, int64_t K, int outer, int *bm, int *bn, int
 hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K, void *out, int out_f32,
                           void *ws, size_t ws_bytes, hipStream_t st);
 
+// OsciReset on a binary32 weight matrix of n elements (rows of a multiple of 128): statistics step and reset
+hipError_t launch_osci_update(const float *W, float *W_prev, float *dist_m, float *dist_q, int64_t n, int first, hipStream_t st);
+hipError_t launch_osci_suppress(float *W, const float *dist_m, const float *dist_q, float tau, int64_t n,
+                                unsigned long long *n_reset, hipStream_t st);
+
 uint64_t stream_key(uint64_t seed, uint32_t tensor_id);
 
 }  // namespace tj

@@ -50,15 +50,6 @@ __device__ __forceinline__ float block_tensor_amax(const KArgs &a, float *red)
     return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-// reciprocals of all E4M3 values (entry 0 = 0, so a zero scale gives all-zero codes)
-__device__ __forceinline__ void fill_inv_table(float *tab)
-{
-    if (threadIdx.x < 128) {
-        float v = e4m3_value(threadIdx.x);
-        tab[threadIdx.x] = (threadIdx.x == 0 || threadIdx.x == 127) ? 0.0f : 1.0f / v;
-    }
-}
-
 // eight consecutive elements of one group -> eight codes in one dword (element 0 in the low nibble)
 template <int ROUND, bool SUP>
 __device__ __forceinline__ uint32_t quant8(const float (&x)[8], float r, uint32_t quad0, uint32_t k0, uint32_t k1)

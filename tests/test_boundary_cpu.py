@@ -229,3 +229,16 @@ def test_static_scratch_entry_rejects_bad_arguments_and_oversized_products(lib):
     assert b"static" in lib.nvfp4_strerror(B.ERR_SCRATCH)
     header = open(os.path.join(ROOT, "include", "tjnvfp4.h")).read()
     assert "#define NVFP4_STATIC_SCRATCH_BYTES (64u << 20)" in header and B.STATIC_SCRATCH_BYTES == 64 << 20
+
+
+def test_osci_calls_reject_bad_arguments(lib):
+    up = lambda W=FAKE, Wp=FAKE, dm=FAKE, dq=FAKE, Cc=4, D=128, t0=1: lib.nvfp4_osci_update(W, Wp, dm, dq, Cc, D, t0, None)
+    assert up(W=None) == -1 and up(dq=None) == -1
+    assert up(D=192) == -2 and up(Cc=-1) == -2
+    assert up(Wp=FAKE + 4) == -5
+    assert up(t0=-1) == -3
+    sp = lambda W=FAKE, dm=FAKE, dq=FAKE, tau=8.0, Cc=4, D=128, n=None: lib.nvfp4_osci_suppress(W, dm, dq, tau, Cc, D, n, None)
+    assert sp(dm=None) == -1
+    assert sp(D=64) == -2
+    assert sp(tau=0.0) == -3 and sp(tau=float("nan")) == -3
+    assert sp(n=FAKE + 4) == -5
