@@ -231,7 +231,7 @@ def gemm_nt(qa: NVFP4, qb: NVFP4, rows_a=None, rows_b=None):
 
 def tensor_id(layer_id: int, quantizer_index: int) -> int:
     """Stream id of quantizer Q^(k) of a layer (k = 1..6 as numbered in Sec. 2.3)."""
-    return layer_id * 8 + quantizer_index
+    return layer_id * 16 + quantizer_index
 
 
 # ----- the linear layer of Sec. 2.3 ------------------------------------------------------
@@ -245,7 +245,7 @@ def linear_fwd(X_bits, W_bits, outer: int = OUTER_TENSOR):
 
 def rht_id(layer_id: int, product: str):
     """Stream id of the random signs of a layer's backward product (Sec. 4.1): "dx" (signs along C) or "dw" (along N)."""
-    return layer_id * 8 + (7 if product == "dx" else 0)
+    return layer_id * 16 + (7 if product == "dx" else 8)
 
 
 def linear_bwd_dx_operands(dY_bits, Wq: NVFP4, seed: int, layer_id: int, outer: int = OUTER_TENSOR, rht: bool = False):
@@ -294,3 +294,35 @@ def osci_suppress(W, dist_m, dist_q, tau: float) -> int:
     if n < 0:
         raise ValueError("oracle_osci_suppress: bad shape")
     return int(n)
+
+
+# ----- OutControl split linear (Sec. 4.2) -------------------------------------------------------
+
+def outctl_fwd(X_lo_bits, W_lo_bits, X_hp_bits, W_hp_bits, outer: int = OUTER_TENSOR):
+    """Y = Q1(X_lo) x Q2(W_lo^T) + X_hp x W_hp^T: returns (Xq, Wq, Y, abs) with Y in binary64 (the bf16 values of the
+    outlier channels are exact there) and abs = sum_k |a||b| over both terms (for tolerance scaling)."""
+    Xq, Wq = linear_fwd(X_lo_bits, W_lo_bits, outer=outer)
+    Y, Ab = gemm_nt(Xq, Wq)
+    Xh, Wh = bf16_to_f32(X_hp_bits).astype(np.float64), bf16_to_f32(W_hp_bits).astype(np.float64)
+    if Xh.shape[1]:
+        Yh, Abh = gemm_nt_f64(Xh, Wh)
+        Y, Ab = Y + Yh, Ab + Abh
+    return Xq, Wq, Y, Ab
+
+
+def outctl_bwd(dY_bits, Xq: NVFP4, Wq: NVFP4, X_hp_bits, W_hp_bits, seed: int, layer_id: int, rht: bool = False):
+    """The four gradients of the split layer, each as (value, abs) in binary64:
+    dX_lo = Q3(dY) x Q4(W_hat_lo), dX_hp = Q3(dY) x Q4(W_hp) (NVFP4, one Q3 operand),
+    dW_lo = Q5(dY^T) x Q6(X_hat_lo) (NVFP4), dW_hp = dY^T x X_hp (bf16 values, exact products)."""
+    outer = Xq.outer
+    o3, o4 = linear_bwd_dx_operands(dY_bits, Wq, seed, layer_id, outer=outer, rht=rht)
+    o5, o6 = linear_bwd_dw_operands(dY_bits, Xq, seed, layer_id, outer=outer, rht=rht)
+    res = {"dX_lo": gemm_nt(o3, o4), "dW_lo": gemm_nt(o5, o6)}
+    if X_hp_bits.shape[1]:
+        o4h = quantize_bf16(W_hp_bits, 1, SR, outer=outer, seed=seed, tensor_id=tensor_id(layer_id, 9),
+                            rht_id=rht_id(layer_id, "dx") if rht else None)
+        res["dX_hp"] = gemm_nt(o3, o4h)
+        dYT = np.ascontiguousarray(bf16_to_f32(dY_bits).astype(np.float64).T)
+        XhT = np.ascontiguousarray(bf16_to_f32(X_hp_bits).astype(np.float64).T)
+        res["dW_hp"] = gemm_nt_f64(dYT, XhT)
+    return res
