@@ -37,6 +37,9 @@ def parse():
                     help="outer scale of every operand: per tensor, or the paper's 1 x 128 blocks")
     ap.add_argument("--rht", action="store_true",
                     help="random Hadamard transform (block 16) on both operands of both backward products; needs --outer block128")
+    ap.add_argument("--outctl", type=int, default=0, metavar="CHANNELS",
+                    help="outlier-control split layer: this many input channels of every linear (those with the largest "
+                         "activation norm; a multiple of 128) stay in bf16")
     ap.add_argument("--no-extras", action="store_true", help="skip the side measurements (other workloads, quantizer bandwidth)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -55,21 +58,30 @@ def dev_bf16(torch, np, bits, dev):
 class Workload:
     """Resident inputs, contexts, outputs and workspaces of every linear of one workload, and its step."""
 
-    def __init__(self, tj, wl, np, torch, dev, name, outer, rht=False):
+    def __init__(self, tj, wl, np, torch, dev, name, outer, rht=False, n_hp=0):
         B = tj.binding
-        self.tj, self.B, self.name, self.outer, self.rht = tj, B, name, outer, rht
+        self.tj, self.B, self.name, self.outer, self.rht, self.n_hp = tj, B, name, outer, rht, n_hp
         self.layers = []
         for li, (lname, N, D, C, seed, kind) in enumerate(wl.config_linears(name)):
             Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed, kind)
             L = dict(name=lname, N=N, D=D, C=C, li=li, X=dev_bf16(torch, np, Xb, dev), W=dev_bf16(torch, np, Wb, dev),
                      dY=dev_bf16(torch, np, dYb, dev))
+            if n_hp:
+                Xl, Wl, Xh, Wh, _ = wl.outlier_channel_split(Xb, Wb, n_hp)
+                L.update(X=dev_bf16(torch, np, Xl, dev), W=dev_bf16(torch, np, Wl, dev), Xh=dev_bf16(torch, np, Xh, dev),
+                         Wh=dev_bf16(torch, np, Wh, dev))
+                D = D - n_hp
+                L["outs"] = [torch.empty(sh, dtype=torch.bfloat16, device=dev) for sh in ((N, D), (N, n_hp), (C, D), (C, n_hp))]
+                L["ws"] = tj.alloc_workspace(max(B.lib().nvfp4_outctl_workspace_bytes(b, N, D, n_hp, C, outer, B.OUT_BF16)
+                                                 for b in (0, 1)))
             L["Xq"] = tj.alloc_nvfp4(N, D, outer)
             L["Wq"] = tj.alloc_nvfp4(C, D, outer)
             L["Y"] = torch.empty((N, C), dtype=torch.bfloat16, device=dev)
             L["dX"] = torch.empty((N, D), dtype=torch.bfloat16, device=dev)
             L["dW"] = torch.empty((C, D), dtype=torch.bfloat16, device=dev)
-            nbytes = max(tj.workspace_bytes(op, N, D, C, outer) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD))
-            L["ws"] = tj.alloc_workspace(nbytes)
+            if not n_hp:
+                nbytes = max(tj.workspace_bytes(op, N, D, C, outer) for op in (B.OP_LINEAR_FWD, B.OP_LINEAR_BWD))
+                L["ws"] = tj.alloc_workspace(nbytes)
             self.layers.append(L)
         self.flops = wl.config_flops(name)
         # lower bound of a step from the two rooflines, per linear: bf16 reads of X, W, dY, packed operands written
@@ -83,6 +95,14 @@ class Workload:
 
     def step(self, sr_seed):
         tj, B = self.tj, self.B
+        if self.n_hp:
+            for L in self.layers:
+                tj.outctl_fwd(L["X"], L["W"], L["Xh"], L["Wh"], B.OUT_BF16, outer=self.outer, Y=L["Y"], Xq=L["Xq"], Wq=L["Wq"],
+                              ws=L["ws"])
+            for L in reversed(self.layers):
+                tj.outctl_bwd(L["dY"], L["Xq"], L["Wq"], L["Xh"], L["Wh"], sr_seed, L["li"], B.OUT_BF16, rht=self.rht, ws=L["ws"],
+                              outs=L["outs"])
+            return
         for L in self.layers:
             tj.linear_fwd(L["X"], L["W"], B.OUT_BF16, Y=L["Y"], Xq=L["Xq"], Wq=L["Wq"], ws=L["ws"], outer=self.outer)
         for L in reversed(self.layers):
@@ -153,7 +173,7 @@ def main():
     if args.rht and outer != B.OUTER_BLOCK128:
         print("bench.py: --rht needs --outer block128", file=sys.stderr)
         sys.exit(2)
-    w = Workload(tj, wl, np, torch, dev, args.workload, outer, args.rht)
+    w = Workload(tj, wl, np, torch, dev, args.workload, outer, args.rht, args.outctl)
     ms_per_step = w.time_steps(torch, args.steps, args.warmup)
     value = w.flops / (ms_per_step * 1e-3) / 1e12
     layers = w.layers
@@ -164,10 +184,10 @@ def main():
     # one launch of this kernel).
     gemm_jobs = []
     for L in layers:
-        dYq = tj.quantize(L["dY"], 0, B.ROUND_SR, seed=1, tensor_id=L["li"] * 8 + 3, outer=outer)
-        Wq2 = tj.quantize(L["Wq"], 1, B.ROUND_SR, seed=1, tensor_id=L["li"] * 8 + 4, outer=outer)
-        dYq2 = tj.quantize(L["dY"], 1, B.ROUND_SR, seed=1, tensor_id=L["li"] * 8 + 5, outer=outer)
-        Xq2 = tj.quantize(L["Xq"], 1, B.ROUND_SR, seed=1, tensor_id=L["li"] * 8 + 6, outer=outer)
+        dYq = tj.quantize(L["dY"], 0, B.ROUND_SR, seed=1, tensor_id=L["li"] * 16 + 3, outer=outer)
+        Wq2 = tj.quantize(L["Wq"], 1, B.ROUND_SR, seed=1, tensor_id=L["li"] * 16 + 4, outer=outer)
+        dYq2 = tj.quantize(L["dY"], 1, B.ROUND_SR, seed=1, tensor_id=L["li"] * 16 + 5, outer=outer)
+        Xq2 = tj.quantize(L["Xq"], 1, B.ROUND_SR, seed=1, tensor_id=L["li"] * 16 + 6, outer=outer)
         for A, Bt, out in ((L["Xq"], L["Wq"], L["Y"]), (dYq, Wq2, L["dX"]), (dYq2, Xq2, L["dW"])):
             nws = tj.workspace_bytes(B.OP_GEMM, A.rows, A.K, Bt.rows, outer)
             gemm_jobs.append((A, Bt, out, tj.alloc_workspace(max(nws, 16)), 2.0 * A.rows * Bt.rows * A.K))
@@ -206,7 +226,7 @@ def main():
            "config": {"workload": args.workload, "tokens": layers[0]["N"],
                       "linears": [[L["name"], L["D"], L["C"]] for L in layers],
                       "outer_scale": "per-tensor" if outer == B.OUTER_TENSOR else "1x128 blocks",
-                      "rht": bool(args.rht),
+                      "rht": bool(args.rht), "bf16_outlier_channels": args.outctl,
                       "flops_per_step": w.flops},
            "frac_of_mfma_peak": round(value / MFMA_F16_PEAK_TFLOPS, 4),
            "frac_of_roofline_lower_bound": round(w.t_min * 1e3 / ms_per_step, 4),

@@ -170,9 +170,9 @@ int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t
 
 /*
  * Input gradient (Sec. 2.3, second line): dX [N x D] = Q3_S(dY) x Q4_S(W_hat); dY [N x C] bf16, W_hat = Wq_ctx of
- * the forward call, both re-grouped along C with stochastic rounding.  Streams: tensor ids layer_id*8+3 and +4.
+ * the forward call, both re-grouped along C with stochastic rounding.  Streams: tensor ids layer_id*16+3 and +4.
  * rht = 1 (Sec. 4.1 / 4.2; contexts with 1 x 128 outer blocks only): both operands are first transformed along C,
- * dX = Q3(dY S H) x Q4(H^T S^T W_hat), signs of stream layer_id*8+7.
+ * dX = Q3(dY S H) x Q4(H^T S^T W_hat), signs of stream layer_id*16+7.
  */
 int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, int64_t D, int64_t C,
                         void *dX, int out_dtype, uint64_t seed, uint32_t layer_id, int rht,
@@ -180,8 +180,8 @@ int nvfp4_linear_bwd_dx(const void *dY, const nvfp4_tensor *Wq_ctx, int64_t N, i
 
 /*
  * Weight gradient (Sec. 2.3, third line): dW [C x D] = Q5_S(dY^T) x Q6_S(X_hat); both operands re-grouped along N
- * with stochastic rounding.  Streams: tensor ids layer_id*8+5 and +6.  rht = 1: both operands are first transformed
- * along N, dW = Q5(dY^T S H) x Q6(H^T S^T X_hat), signs of stream layer_id*8+0.
+ * with stochastic rounding.  Streams: tensor ids layer_id*16+5 and +6.  rht = 1: both operands are first transformed
+ * along N, dW = Q5(dY^T S H) x Q6(H^T S^T X_hat), signs of stream layer_id*16+8.
  * Limits: N % 64 == 0 (N % 128 == 0 in BLOCK128 mode) and N <= 2^22 (reduction length); C % 8 == 0; D % 16 == 0.
  */
 int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, int64_t D, int64_t C,
@@ -198,6 +198,31 @@ int nvfp4_linear_bwd_dw(const void *dY, const nvfp4_tensor *Xq_ctx, int64_t N, i
 int nvfp4_linear_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx,
                      int64_t N, int64_t D, int64_t C, void *dX, void *dW, int out_dtype,
                      uint64_t seed, uint32_t layer_id, int rht, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * OutControl split linear (Sec. 4.2): a static set A of outlier channels of the activation stays in high precision
+ * (bf16 here), the rest runs in NVFP4.  Because the set is fixed once, the caller keeps the two column sets as separate
+ * row-major bf16 tensors: X_lo [N x D_lo], W_lo [C x D_lo] (ordinary channels) and X_hp [N x D_hp], W_hp [C x D_hp]
+ * (outlier channels; D_hp % 32 == 0, may be 0).
+ *   forward:  Y = Q1(X_lo) x Q2(W_lo^T) + X_hp x W_hp^T  (the second product on the bf16 matrix path, FP32 accumulate;
+ *             the sum is formed in FP32 and rounded once to out_dtype).  Xq_ctx / Wq_ctx describe the ordinary channels.
+ *   backward: dX = Q3(dY) x Q4(W_hat) over ALL input channels in NVFP4: dX_lo [N x D_lo] from the re-quantized context,
+ *             dX_hp [N x D_hp] from W_hp quantized column-wise (stream id layer_id*16+9), both against one Q3 operand;
+ *             dW_lo [C x D_lo] = Q5(dY^T) x Q6(X_hat_lo) in NVFP4; dW_hp [C x D_hp] = dY^T x X_hp in bf16.
+ *             rht as in nvfp4_linear_bwd (on the four NVFP4 operands and on Q4 of W_hp).  With per-tensor outer scales
+ *             W_hat's two column sets each get a scale of their own; with 1 x 128 outer blocks (the paper's setting) the
+ *             split changes nothing, every output row of Q4 being scaled by itself.
+ * ws: nvfp4_outctl_workspace_bytes(backward, ...).  Limits as for nvfp4_linear_fwd / nvfp4_linear_bwd with D = D_lo.
+ */
+int nvfp4_outctl_fwd(const void *X_lo, const void *W_lo, const void *X_hp, const void *W_hp, int64_t N, int64_t D_lo,
+                     int64_t D_hp, int64_t C, void *Y, int out_dtype, nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx,
+                     int outer_mode, void *ws, size_t ws_bytes, void *stream);
+int nvfp4_outctl_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx, const void *X_hp,
+                     const void *W_hp, int64_t N, int64_t D_lo, int64_t D_hp, int64_t C, void *dX_lo, void *dX_hp,
+                     void *dW_lo, void *dW_hp, int out_dtype, uint64_t seed, uint32_t layer_id, int rht, void *ws,
+                     size_t ws_bytes, void *stream);
+size_t nvfp4_outctl_workspace_bytes(int backward, int64_t N, int64_t D_lo, int64_t D_hp, int64_t C, int outer_mode,
+                                    int out_dtype);
 
 /*
  * OsciReset (Sec. 3.2-3.3) for one weight matrix of binary32 master weights W [C x D], all arrays device memory of

@@ -24,7 +24,7 @@ SRC_BF16, SRC_NVFP4 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW, OP_LINEAR_BWD = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_gemm_nt_static", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd", "nvfp4_osci_update", "nvfp4_osci_suppress",
+EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_gemm_nt_static", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd", "nvfp4_osci_update", "nvfp4_osci_suppress", "nvfp4_outctl_fwd", "nvfp4_outctl_bwd", "nvfp4_outctl_workspace_bytes",
            "nvfp4_workspace_bytes", "nvfp4_gemm_plan", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
 
 
@@ -75,6 +75,14 @@ def lib():
         L.nvfp4_linear_bwd.restype = i32
         L.nvfp4_linear_bwd.argtypes = [vp, C.POINTER(CTensor), C.POINTER(CTensor), i64, i64, i64, vp, vp, i32, u64, u32,
                                        i32, vp, sz, vp]
+        L.nvfp4_outctl_fwd.restype = i32
+        L.nvfp4_outctl_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, i32, C.POINTER(CTensor), C.POINTER(CTensor), i32, vp,
+                                       sz, vp]
+        L.nvfp4_outctl_bwd.restype = i32
+        L.nvfp4_outctl_bwd.argtypes = [vp, C.POINTER(CTensor), C.POINTER(CTensor), vp, vp, i64, i64, i64, i64, vp, vp, vp, vp, i32,
+                                       u64, u32, i32, vp, sz, vp]
+        L.nvfp4_outctl_workspace_bytes.restype = sz
+        L.nvfp4_outctl_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
         L.nvfp4_osci_update.restype = i32
         L.nvfp4_osci_update.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
         L.nvfp4_osci_suppress.restype = i32
@@ -358,3 +366,49 @@ def osci_suppress(W: torch.Tensor, dist_m: torch.Tensor, dist_q: torch.Tensor, t
         assert n_reset.dtype == torch.int64 and n_reset.numel() == 1 and n_reset.is_cuda
     _check(lib().nvfp4_osci_suppress(_ptr(W), _ptr(dist_m), _ptr(dist_q), tau, Cc, D, _ptr(n_reset), _stream()),
            "nvfp4_osci_suppress")
+
+
+def outctl_fwd(X_lo, W_lo, X_hp, W_hp, out_dtype: int = OUT_BF16, *, outer: int = OUTER_TENSOR, Y=None, Xq=None, Wq=None, ws=None):
+    """nvfp4_outctl_fwd: Y = Q1(X_lo) Q2(W_lo)^T + X_hp W_hp^T (Sec. 4.2); returns (Y, Xq, Wq) of the ordinary channels."""
+    for t, n in ((X_lo, "X_lo"), (W_lo, "W_lo"), (X_hp, "X_hp"), (W_hp, "W_hp")):
+        _check_bf16(t, n)
+    N, D_lo = X_lo.shape
+    Cc, D_hp = W_hp.shape
+    assert W_lo.shape == (Cc, D_lo) and X_hp.shape == (N, D_hp)
+    dev = X_lo.device
+    Y = _out_tensor(N, Cc, out_dtype, dev) if Y is None else Y
+    _check_out(Y, (N, Cc), out_dtype, "Y")
+    Xq = alloc_nvfp4(N, D_lo, outer, dev) if Xq is None else Xq
+    Wq = alloc_nvfp4(Cc, D_lo, outer, dev) if Wq is None else Wq
+    if ws is None:
+        ws = alloc_workspace(lib().nvfp4_outctl_workspace_bytes(0, N, D_lo, D_hp, Cc, outer, out_dtype), dev)
+    cx, cw = Xq.c_struct(), Wq.c_struct()
+    rc = lib().nvfp4_outctl_fwd(_ptr(X_lo), _ptr(W_lo), _ptr(X_hp), _ptr(W_hp), N, D_lo, D_hp, Cc, _ptr(Y), out_dtype,
+                                C.byref(cx), C.byref(cw), outer, _ptr(ws), ws.numel(), _stream())
+    _check(rc, "nvfp4_outctl_fwd")
+    Xq.rows, Xq.K, Xq.outer = cx.rows, cx.K, cx.outer_mode
+    Wq.rows, Wq.K, Wq.outer = cw.rows, cw.K, cw.outer_mode
+    return Y, Xq, Wq
+
+
+def outctl_bwd(dY, Xq: NVFP4Tensor, Wq: NVFP4Tensor, X_hp, W_hp, seed: int, layer_id: int, out_dtype: int = OUT_BF16, *,
+               rht: bool = False, ws=None, outs=None):
+    """nvfp4_outctl_bwd: returns (dX_lo, dX_hp, dW_lo, dW_hp) (written into `outs` when given)."""
+    for t, n in ((dY, "dY"), (X_hp, "X_hp"), (W_hp, "W_hp")):
+        _check_bf16(t, n)
+    N, Cc = dY.shape
+    D_lo, D_hp = Xq.K, X_hp.shape[1]
+    dev = dY.device
+    shapes = [(N, D_lo), (N, D_hp), (Cc, D_lo), (Cc, D_hp)]
+    if outs is None:
+        outs = [_out_tensor(a, b, out_dtype, dev) for a, b in shapes]
+    for t, sh in zip(outs, shapes):
+        _check_out(t, sh, out_dtype, "gradient output")
+    if ws is None:
+        ws = alloc_workspace(lib().nvfp4_outctl_workspace_bytes(1, N, D_lo, D_hp, Cc, Xq.outer, out_dtype), dev)
+    cx, cw = Xq.c_struct(), Wq.c_struct()
+    rc = lib().nvfp4_outctl_bwd(_ptr(dY), C.byref(cx), C.byref(cw), _ptr(X_hp), _ptr(W_hp), N, D_lo, D_hp, Cc, _ptr(outs[0]),
+                                _ptr(outs[1]), _ptr(outs[2]), _ptr(outs[3]), out_dtype, seed, layer_id, int(rht), _ptr(ws),
+                                ws.numel(), _stream())
+    _check(rc, "nvfp4_outctl_bwd")
+    return tuple(outs)

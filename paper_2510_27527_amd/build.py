@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtjnvfp4.so")
 # (source, object name, extra flags): the product kernel's instantiations are compiled in twelve slices, in parallel
-SOURCES = [("api.hip", "api.o", []), ("quant.hip", "quant.o", []), ("osci.hip", "osci.o", []), ("gemm.hip", "gemm.o", [])] + [
+SOURCES = [("api.hip", "api.o", []), ("quant.hip", "quant.o", []), ("osci.hip", "osci.o", []), ("hp.hip", "hp.o", []), ("gemm.hip", "gemm.o", [])] + [
     ("gemm_inst.hip", "gemm_inst_ps%d_out%d_outer%d.o" % (ps, out, outer),
      ["-DTJ_GEMM_PS=%d" % ps, "-DTJ_GEMM_OUT=%d" % out, "-DTJ_GEMM_OUTER=%d" % outer])
     for outer in (0, 1) for ps in (1, 0) for out in (0, 2, 1)]

@@ -485,6 +485,123 @@ int nvfp4_gemm_nt_static(const nvfp4_tensor *A, const nvfp4_tensor *B, void *Out
     return run_gemm(A, B, Out, out_dtype, ws, need, static_cast<hipStream_t>(stream));
 }
 
+// ---- OutControl split linear (Sec. 4.2) -------------------------------------------------------------------------
+
+static nvfp4_qcfg bwd_cfg(uint64_t seed, uint32_t layer_id, int k, int outer, int rht);
+
+static size_t outctl_fwd_bytes(int64_t N, int64_t D_lo, int64_t C, int outer, int out_dtype)
+{
+    return nvfp4_workspace_bytes(NVFP4_OP_LINEAR_FWD, N, D_lo, C, outer) +
+           (out_dtype == NVFP4_OUT_F32 ? 0 : align_up((size_t)(N * C) * sizeof(float)));
+}
+
+static size_t outctl_bwd_bytes(int64_t N, int64_t D_lo, int64_t D_hp, int64_t C, int outer)
+{
+    const size_t g1 = align_up(gemm_workspace_bytes(N, D_lo, C, outer)), g2 = align_up(gemm_workspace_bytes(C, D_lo, N, outer));
+    const size_t g3 = align_up(gemm_workspace_bytes(N, D_hp, C, outer));
+    size_t g = g1 > g2 ? g1 : g2;
+    g = g > g3 ? g : g3;
+    return 2 * partials_bytes() + packed_bytes(N, C, outer) + packed_bytes(D_lo, C, outer) + packed_bytes(D_hp, C, outer) +
+           packed_bytes(C, N, outer) + packed_bytes(D_lo, N, outer) + align_up((size_t)(N * C) * 2) +
+           align_up((size_t)(N * D_hp) * 2) + g;
+}
+
+size_t nvfp4_outctl_workspace_bytes(int backward, int64_t N, int64_t D_lo, int64_t D_hp, int64_t C, int outer_mode, int out_dtype)
+{
+    if (N < 0 || D_lo < 0 || D_hp < 0 || C < 0 || !valid_outer(outer_mode)) return 0;
+    return backward ? outctl_bwd_bytes(N, D_lo, D_hp, C, outer_mode) : outctl_fwd_bytes(N, D_lo, C, outer_mode, out_dtype);
+}
+
+int nvfp4_outctl_fwd(const void *X_lo, const void *W_lo, const void *X_hp, const void *W_hp, int64_t N, int64_t D_lo,
+                     int64_t D_hp, int64_t C, void *Y, int out_dtype, nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx,
+                     int outer_mode, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!X_hp || !W_hp) return NVFP4_ERR_NULL;
+    if (D_hp < 0 || D_hp % 32 != 0) return NVFP4_ERR_SHAPE;
+    if (!aligned16(X_hp) || !aligned16(W_hp)) return NVFP4_ERR_ALIGN;
+    int rc = check_out(Y, out_dtype);
+    if (rc) return rc;
+    if (N < 0 || D_lo < 0 || C < 0) return NVFP4_ERR_SHAPE;
+    if (!valid_outer(outer_mode)) return NVFP4_ERR_ENUM;
+    if (!ws || ws_bytes < outctl_fwd_bytes(N, D_lo, C, outer_mode, out_dtype)) return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
+    // the FP4 product in FP32 (in Y itself when Y is FP32), then the bf16 term is added and the sum stored
+    const size_t fwd_ws = nvfp4_workspace_bytes(NVFP4_OP_LINEAR_FWD, N, D_lo, C, outer_mode);
+    float *y32 = out_dtype == NVFP4_OUT_F32 ? static_cast<float *>(Y)
+                                            : reinterpret_cast<float *>(static_cast<uint8_t *>(ws) + fwd_ws);
+    rc = nvfp4_linear_fwd(X_lo, W_lo, N, D_lo, C, y32, NVFP4_OUT_F32, Xq_ctx, Wq_ctx, outer_mode, ws, fwd_ws, stream);
+    if (rc) return rc;
+    return launch_hp_gemm_nt(X_hp, W_hp, N, C, D_hp, y32, Y, out_dtype == NVFP4_OUT_F32, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_outctl_bwd(const void *dY, const nvfp4_tensor *Xq_ctx, const nvfp4_tensor *Wq_ctx, const void *X_hp,
+                     const void *W_hp, int64_t N, int64_t D_lo, int64_t D_hp, int64_t C, void *dX_lo, void *dX_hp,
+                     void *dW_lo, void *dW_hp, int out_dtype, uint64_t seed, uint32_t layer_id, int rht, void *ws,
+                     size_t ws_bytes, void *stream)
+{
+    if (!dY || !Xq_ctx || !Wq_ctx || !X_hp || !W_hp) return NVFP4_ERR_NULL;
+    if (N < 0 || D_lo < 0 || D_hp < 0 || C < 0) return NVFP4_ERR_SHAPE;
+    if (check_reduction(C) || check_reduction(N) || D_hp % 32 != 0) return NVFP4_ERR_SHAPE;
+    int rc = check_out(dX_lo, out_dtype);
+    if (!rc) rc = check_out(dX_hp, out_dtype);
+    if (!rc) rc = check_out(dW_lo, out_dtype);
+    if (!rc) rc = check_out(dW_hp, out_dtype);
+    if (rc) return rc;
+    if (Wq_ctx->rows != C || Wq_ctx->K != D_lo || Xq_ctx->rows != N || Xq_ctx->K != D_lo) return NVFP4_ERR_MISMATCH;
+    if (Wq_ctx->outer_mode != Xq_ctx->outer_mode) return NVFP4_ERR_MISMATCH;
+    const int outer = Xq_ctx->outer_mode;
+    if (!valid_outer(outer)) return NVFP4_ERR_ENUM;
+    if (!aligned16(dY) || !aligned16(X_hp) || !aligned16(W_hp)) return NVFP4_ERR_ALIGN;
+    if (!ws || ws_bytes < outctl_bwd_bytes(N, D_lo, D_hp, C, outer)) return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(ws)) return NVFP4_ERR_ALIGN;
+    Carver cv{static_cast<uint8_t *>(ws), ws_bytes, 0};
+    float *part = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
+    float *part2 = static_cast<float *>(cv.take(sizeof(float) * kMaxAmaxPartials));
+    nvfp4_tensor q3{}, q4{}, q4h{}, q5{}, q6{};
+    if (!carve_tensor(cv, N, C, outer, &q3) || !carve_tensor(cv, D_lo, C, outer, &q4) || !carve_tensor(cv, D_hp, C, outer, &q4h) ||
+        !carve_tensor(cv, C, N, outer, &q5) || !carve_tensor(cv, D_lo, N, outer, &q6))
+        return NVFP4_ERR_WORKSPACE;
+    void *dYT = cv.take((size_t)(N * C) * 2), *XhT = cv.take((size_t)(N * D_hp) * 2);
+    const size_t g1 = gemm_workspace_bytes(N, D_lo, C, outer), g2 = gemm_workspace_bytes(C, D_lo, N, outer),
+                 g3 = gemm_workspace_bytes(N, D_hp, C, outer);
+    size_t gbytes = g1 > g2 ? g1 : g2;
+    gbytes = gbytes > g3 ? gbytes : g3;
+    void *gws = gbytes ? cv.take(gbytes) : nullptr;
+    if (!dYT || !XhT || (gbytes && !gws)) return NVFP4_ERR_WORKSPACE;
+
+    // the five stochastic quantizers: Q3, Q5 of dY; Q4, Q6 of the forward contexts; Q4 of the outlier channels of W
+    nvfp4_qcfg c3 = bwd_cfg(seed, layer_id, 3, outer, rht), c4 = bwd_cfg(seed, layer_id, 4, outer, rht),
+               c5 = bwd_cfg(seed, layer_id, 5, outer, rht), c6 = bwd_cfg(seed, layer_id, 6, outer, rht),
+               c9 = bwd_cfg(seed, layer_id, 9, outer, rht);
+    QuantPlan p3{}, p4{}, p5{}, p6{}, p9{};
+    rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 0, &c3, &q3, &p3);
+    if (!rc) rc = plan_quantize(Wq_ctx, NVFP4_SRC_NVFP4, C, D_lo, 1, &c4, &q4, &p4);
+    if (!rc) rc = plan_quantize(dY, NVFP4_SRC_BF16, N, C, 1, &c5, &q5, &p5);
+    if (!rc) rc = plan_quantize(Xq_ctx, NVFP4_SRC_NVFP4, N, D_lo, 1, &c6, &q6, &p6);
+    if (!rc && D_hp > 0) rc = plan_quantize(W_hp, NVFP4_SRC_BF16, C, D_hp, 1, &c9, &q4h, &p9);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = run_quantize(dY, p3, &c3, &q3, part, st);
+    if (!rc) rc = run_quantize(dY, p5, &c5, &q5, part, st);
+    if (!rc) rc = run_requant_pair(Wq_ctx, p4, &c4, &q4, Xq_ctx, p6, &c6, &q6, st);
+    if (!rc && D_hp > 0) rc = run_quantize(W_hp, p9, &c9, &q4h, part2, st);
+    if (rc) return rc;
+    // dX over all input channels in FP4 (one Q3 operand serves both column sets); dW of the ordinary channels in FP4
+    rc = run_gemm(&q3, &q4, dX_lo, out_dtype, gws, gbytes, st);
+    if (!rc && D_hp > 0) rc = run_gemm(&q3, &q4h, dX_hp, out_dtype, gws, gbytes, st);
+    if (!rc) rc = run_gemm(&q5, &q6, dW_lo, out_dtype, gws, gbytes, st);
+    if (rc) return rc;
+    // dW of the outlier channels in bf16: dY^T [C x N] times X_hp^T [D_hp x N]^T, the reduction running over tokens
+    if (D_hp > 0 && C > 0) {
+        if (launch_transpose_bf16(dY, dYT, N, C, st) != hipSuccess) return NVFP4_ERR_HIP;
+        if (launch_transpose_bf16(X_hp, XhT, N, D_hp, st) != hipSuccess) return NVFP4_ERR_HIP;
+        if (launch_hp_gemm_nt(dYT, XhT, C, D_hp, N, nullptr, dW_hp, out_dtype == NVFP4_OUT_F32, st) != hipSuccess)
+            return NVFP4_ERR_HIP;
+    }
+    return NVFP4_OK;
+}
+
 static int check_osci(const void *W, const void *a, const void *b, int64_t C, int64_t D)
 {
     if (!W || !a || !b) return NVFP4_ERR_NULL;
@@ -555,9 +672,9 @@ static nvfp4_qcfg bwd_cfg(uint64_t seed, uint32_t layer_id, int k, int outer, in
     c.rounding = NVFP4_ROUND_SR;
     c.outer_mode = outer;
     c.seed = seed;
-    c.tensor_id = layer_id * 8u + (uint32_t)k;
+    c.tensor_id = layer_id * 16u + (uint32_t)k;
     c.rht = rht;
-    c.rht_id = layer_id * 8u + (k <= 4 ? 7u : 0u);      // Q3, Q4: the signs of the dX product; Q5, Q6: of the dW product
+    c.rht_id = layer_id * 16u + (k == 3 || k == 4 || k == 9 ? 7u : 8u);   // the signs of the dX product (Q3, Q4) / of the dW product
     return c;
 }
 

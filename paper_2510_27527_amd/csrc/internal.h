@@ -86,6 +86,12 @@ void gemm_plan(int64_t M, int64_t N, int64_t K, int outer, int *bm, int *bn, int
 hipError_t launch_gemm_nt(const GemmOperand &A, const GemmOperand &B, int64_t K, void *out, int out_f32,
                           void *ws, size_t ws_bytes, hipStream_t st);
 
+// bf16 side of the OutControl split linear: Out[M x N] = addend (optional, f32) + A[M x K] * B[N x K]^T with K % 32 == 0;
+// transpose of a bf16 [R x C] array
+hipError_t launch_hp_gemm_nt(const void *A, const void *B, int64_t M, int64_t N, int64_t K, const float *addend, void *out,
+                             int out_f32, hipStream_t st);
+hipError_t launch_transpose_bf16(const void *src, void *dst, int64_t R, int64_t C, hipStream_t st);
+
 // OsciReset on a binary32 weight matrix of n elements (rows of a multiple of 128): statistics step and reset
 hipError_t launch_osci_update(const float *W, float *W_prev, float *dist_m, float *dist_q, int64_t n, int first, hipStream_t st);
 hipError_t launch_osci_suppress(float *W, const float *dist_m, const float *dist_q, float tau, int64_t n,

@@ -242,3 +242,21 @@ def test_osci_calls_reject_bad_arguments(lib):
     assert sp(D=64) == -2
     assert sp(tau=0.0) == -3 and sp(tau=float("nan")) == -3
     assert sp(n=FAKE + 4) == -5
+
+
+def test_outctl_calls_reject_bad_arguments(lib):
+    X, W = _tensor(128, 128), _tensor(64, 128)
+    fwd = lambda Xh=FAKE, D_hp=32, outer=0, wsb=1 << 40, D_lo=128: lib.nvfp4_outctl_fwd(
+        FAKE, FAKE, Xh, FAKE, 128, D_lo, D_hp, 64, FAKE, 0, C.byref(_tensor()), C.byref(_tensor()), outer, FAKE, wsb, None)
+    assert fwd(Xh=None) == -1
+    assert fwd(D_hp=48) == -2 and fwd(D_lo=100) == -2
+    assert fwd(outer=3) == -3
+    assert fwd(wsb=64) == -4
+    bwd = lambda D_hp=32, x=X, w=W, wsb=1 << 40, rht=0, Cc=64: lib.nvfp4_outctl_bwd(
+        FAKE, C.byref(x), C.byref(w), FAKE, FAKE, 128, 128, D_hp, Cc, FAKE, FAKE, FAKE, FAKE, 0, 0, 0, rht, FAKE, wsb, None)
+    assert bwd(D_hp=40) == -2 and bwd(Cc=32) == -2
+    assert bwd(w=_tensor(64, 256)) == -6
+    assert bwd(wsb=1000) == -4
+    assert bwd(rht=1) == -3                               # per-tensor contexts: the transform is not provided
+    assert lib.nvfp4_outctl_workspace_bytes(1, 128, 128, 32, 64, 0, 0) > lib.nvfp4_workspace_bytes(B.OP_LINEAR_BWD, 128, 128, 64, 0)
+    assert lib.nvfp4_outctl_workspace_bytes(0, 128, 128, 32, 64, 0, 1) == lib.nvfp4_workspace_bytes(B.OP_LINEAR_FWD, 128, 128, 64, 0)

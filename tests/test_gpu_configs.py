@@ -67,7 +67,7 @@ def product_ok(got_rows: torch.Tensor, ref, absref, what):
 def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0, rht=False):
     B = tj.binding
     cfg = cfg + ("/block128" if outer else "") + ("/rht" if rht else "")
-    rid = (lambda prod: li * 8 + (7 if prod == "dx" else 0)) if rht else (lambda prod: None)
+    rid = (lambda prod: li * 16 + (7 if prod == "dx" else 8)) if rht else (lambda prod: None)
     say("[%s %s] N=%d D=%d C=%d: inputs" % (cfg, name, N, D, C))
     Xb, Wb, dYb = wl.linear_inputs(N, D, C, seed, kind)
     X, W, dY = dev_bf16(Xb), dev_bf16(Wb), dev_bf16(dYb)
@@ -86,11 +86,11 @@ def run_full_linear(cfg, name, N, D, C, seed, kind, li, sr_seed, outer=0, rht=Fa
     same_bytes(Wq, oWq, "Q2(W)", check_amax=True)
     say("[%s %s] oracle backward operands" % (cfg, name))
     o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, sr_seed, li, outer=outer, rht=rht)
-    same_bytes(tj.quantize(dY, 0, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 3, outer=outer, rht_id=rid("dx")), o3, "Q3(dY)")
-    same_bytes(tj.quantize(Wq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 4, outer=outer, rht_id=rid("dx")), o4, "Q4(W_hat)")
+    same_bytes(tj.quantize(dY, 0, B.ROUND_SR, seed=sr_seed, tensor_id=li * 16 + 3, outer=outer, rht_id=rid("dx")), o3, "Q3(dY)")
+    same_bytes(tj.quantize(Wq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 16 + 4, outer=outer, rht_id=rid("dx")), o4, "Q4(W_hat)")
     o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, sr_seed, li, outer=outer, rht=rht)
-    same_bytes(tj.quantize(dY, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 5, outer=outer, rht_id=rid("dw")), o5, "Q5(dY^T)")
-    same_bytes(tj.quantize(Xq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 8 + 6, outer=outer, rht_id=rid("dw")), o6, "Q6(X_hat)")
+    same_bytes(tj.quantize(dY, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 16 + 5, outer=outer, rht_id=rid("dw")), o5, "Q5(dY^T)")
+    same_bytes(tj.quantize(Xq, 1, B.ROUND_SR, seed=sr_seed, tensor_id=li * 16 + 6, outer=outer, rht_id=rid("dw")), o6, "Q6(X_hat)")
     dX1 = tj.linear_bwd_dx(dY, Wq, sr_seed, li, B.OUT_BF16, rht=rht)
     dW1 = tj.linear_bwd_dw(dY, Xq, sr_seed, li, B.OUT_BF16, rht=rht)
     torch.cuda.synchronize()

@@ -402,10 +402,10 @@ def test_linear_block128_mode(N, D, C):
     check_product(Y, *oracle.gemm_nt(oXq, oWq), "Y block128")
     o3, o4 = oracle.linear_bwd_dx_operands(dYb, oWq, 5, 2, outer=O)
     o5, o6 = oracle.linear_bwd_dw_operands(dYb, oXq, 5, 2, outer=O)
-    assert_same(tj.quantize(dY, 0, B.ROUND_SR, seed=5, tensor_id=19, outer=B.OUTER_BLOCK128), o3, "Q3 block128")
-    assert_same(tj.quantize(Wq, 1, B.ROUND_SR, seed=5, tensor_id=20, outer=B.OUTER_BLOCK128), o4, "Q4 block128")
-    assert_same(tj.quantize(dY, 1, B.ROUND_SR, seed=5, tensor_id=21, outer=B.OUTER_BLOCK128), o5, "Q5 block128")
-    assert_same(tj.quantize(Xq, 1, B.ROUND_SR, seed=5, tensor_id=22, outer=B.OUTER_BLOCK128), o6, "Q6 block128")
+    assert_same(tj.quantize(dY, 0, B.ROUND_SR, seed=5, tensor_id=35, outer=B.OUTER_BLOCK128), o3, "Q3 block128")
+    assert_same(tj.quantize(Wq, 1, B.ROUND_SR, seed=5, tensor_id=36, outer=B.OUTER_BLOCK128), o4, "Q4 block128")
+    assert_same(tj.quantize(dY, 1, B.ROUND_SR, seed=5, tensor_id=37, outer=B.OUTER_BLOCK128), o5, "Q5 block128")
+    assert_same(tj.quantize(Xq, 1, B.ROUND_SR, seed=5, tensor_id=38, outer=B.OUTER_BLOCK128), o6, "Q6 block128")
     dX = tj.linear_bwd_dx(dY, Wq, 5, 2, B.OUT_F32)
     dW = tj.linear_bwd_dw(dY, Xq, 5, 2, B.OUT_F32)
     check_product(dX, *oracle.gemm_nt(o3, o4), "dX block128")
@@ -568,10 +568,10 @@ def test_backward_operands_match_oracle_bitwise():
     dY = dev_bf16(dYb)
     Xq = tj.quantize(dev_bf16(Xb), 0, 0)
     Wq = tj.quantize(dev_bf16(Wb), 0, 0)
-    assert_same(tj.quantize(dY, 0, 1, seed=13, tensor_id=7 * 8 + 3), o3, "Q3")
-    assert_same(tj.quantize(Wq, 1, 1, seed=13, tensor_id=7 * 8 + 4), o4, "Q4")
-    assert_same(tj.quantize(dY, 1, 1, seed=13, tensor_id=7 * 8 + 5), o5, "Q5")
-    assert_same(tj.quantize(Xq, 1, 1, seed=13, tensor_id=7 * 8 + 6), o6, "Q6")
+    assert_same(tj.quantize(dY, 0, 1, seed=13, tensor_id=7 * 16 + 3), o3, "Q3")
+    assert_same(tj.quantize(Wq, 1, 1, seed=13, tensor_id=7 * 16 + 4), o4, "Q4")
+    assert_same(tj.quantize(dY, 1, 1, seed=13, tensor_id=7 * 16 + 5), o5, "Q5")
+    assert_same(tj.quantize(Xq, 1, 1, seed=13, tensor_id=7 * 16 + 6), o6, "Q6")
 
 
 def test_same_seed_same_bytes_other_seed_other_bytes():

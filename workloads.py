@@ -25,7 +25,7 @@ import numpy as np
 
 __all__ = [
     "f32_to_bf16", "bf16_to_f32", "normal_bf16", "student_t_bf16",
-    "outlier_channel_bf16", "linear_inputs", "CONFIGS", "config_linears",
+    "outlier_channel_bf16", "linear_inputs", "outlier_channel_split", "CONFIGS", "config_linears",
 ]
 
 
@@ -88,6 +88,17 @@ def linear_inputs(N: int, D: int, C: int, seed: int, kind: str = "block"):
     else:
         raise ValueError(kind)
     return X, W, dY
+
+
+def outlier_channel_split(X: np.ndarray, W: np.ndarray, n_hp: int):
+    """The static channel split of the outlier-control layer: the n_hp input channels with the largest activation
+    l2-norm go to the high-precision set, the rest stay; both tensors are split the same way, column order kept.
+    Returns (X_lo, W_lo, X_hp, W_hp, hp_columns) as C-contiguous bf16 bit arrays."""
+    norms = (bf16_to_f32(X).astype(np.float64) ** 2).sum(axis=0)
+    hp = np.sort(np.argsort(-norms, kind="stable")[:n_hp])
+    lo = np.setdiff1d(np.arange(X.shape[1]), hp)
+    c = np.ascontiguousarray
+    return c(X[:, lo]), c(W[:, lo]), c(X[:, hp]), c(W[:, hp]), hp
 
 
 # name -> dict(tokens, linears=[(name, D_in, C_out)], kind, seed)
