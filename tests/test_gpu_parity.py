@@ -333,6 +333,38 @@ def test_gemm_every_kernel_instantiation(key, shape, out_dtype):
     check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm %dx%dx%d" % (M, N, K))
 
 
+# (outer mode, M, N, K, tile): whole tiles, K a multiple of 256, more workgroups than the chip holds of that tile at
+# once and not a multiple of that number, so tiles start and end at different times on one compute unit.  K = 256 is the
+# shortest reduction with paired scale fetch (two stages, one scale pair), 768 a typical short one.
+WALK_SHAPES = [(0, 6016, 4096, 256, (128, 128)), (0, 4736, 3456, 256, (128, 192)), (0, 3200, 5120, 256, (128, 256)),
+               (0, 5120, 3200, 256, (256, 128)), (0, 4352, 5888, 256, (256, 256)), (0, 4352, 5888, 768, None),
+               (0, 4736, 3456, 512, None), (1, 6016, 4096, 256, (128, 128)), (1, 4736, 3456, 256, (128, 192)),
+               (1, 3200, 5120, 256, (128, 256)), (1, 2816, 4480, 256, (256, 128)), (1, 2816, 4480, 768, None)]
+
+
+@pytest.mark.parametrize("outer,M,N,K,tile", WALK_SHAPES)
+@pytest.mark.parametrize("out_dtype", [0, 1])
+def test_gemm_more_tiles_than_resident_workgroups(outer, M, N, K, tile, out_dtype):
+    pm, pn, split = tj.binding.gemm_plan(M, N, K, outer)
+    assert M % pm == 0 and N % pn == 0 and split == 1 and (tile is None or (pm, pn) == tile)
+    resident = 256 * {(256, 256): 1, (256, 128): 1, (128, 256): 1, (128, 128): 3, (128, 192): 2}[(pm, pn)]
+    assert (M // pm) * (N // pn) > resident
+    if outer:
+        A = oracle.quantize_bf16(_block_operand(M, K, 730 + N, 1.0), 0, 0, outer=oracle.OUTER_BLOCK128)
+        B = oracle.quantize_bf16(_block_operand(N, K, 731 + M, 0.02), 0, 1, outer=oracle.OUTER_BLOCK128, seed=6)
+    else:
+        A = oracle.quantize_bf16(wl.normal_bf16((M, K), 1.0, 730 + N, 1e-2, 50.0), 0, 0)
+        B = oracle.quantize_bf16(wl.normal_bf16((N, K), 0.02, 731 + M), 0, 1, seed=6)
+    got = tj.gemm_nt(to_dev(A), to_dev(B), out_dtype)
+    torch.cuda.synchronize()
+    # rows from every tile row: first and last row of each, plus random ones
+    rng = np.random.default_rng(M + 7 * N + K)
+    tiles = np.arange(M // pm) * pm
+    rows = np.unique(np.concatenate([tiles, tiles + pm - 1, rng.choice(M, 32, replace=False)]))
+    ref, absref = oracle.gemm_nt(A, B, rows_a=rows)
+    check_product(got[torch.from_numpy(rows).cuda()], ref, absref, "gemm many tiles %dx%dx%d" % (M, N, K))
+
+
 def _block_operand(rows, K, seed, std):
     """an operand with 1 x 128 outer blocks whose outer scales differ widely from block to block (each 128-block of each
     row gets its own magnitude, 2^-6 .. 2^6 times the base law; a few blocks are all zero)"""
