@@ -89,3 +89,23 @@ def test_bad_arguments():
         tj.outctl_fwd(a[0], a[1], bad, badw)
     assert e.value.code == -2
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("N,D_lo,D_hp,C", [(3648, 64, 96, 3520), (64, 64, 3520, 3648)])
+@pytest.mark.parametrize("out_dtype", [1, 0])
+def test_high_precision_product_with_256x256_tiles(N, D_lo, D_hp, C, out_dtype):
+    """outputs of more than 192 tiles of 256 x 256 take the large-tile instantiation of the bf16 product: the forward term
+    (with the FP4 product as addend) in the first case, the weight gradient of the outlier channels (no addend) in the
+    second; both ragged in both directions"""
+    import paper_2510_27527_amd as tj
+    Xl, Wl, Xh, Wh, dYb = inputs(N, D_lo, D_hp, C, 11 + N)
+    args = [dev_bf16(a) for a in (Xl, Wl, Xh, Wh)]
+    Y, Xq, Wq = tj.outctl_fwd(*args, out_dtype)
+    oXq, oWq, Yref, Yabs = oracle.outctl_fwd(Xl, Wl, Xh, Wh)
+    torch.cuda.synchronize()
+    check(Y, Yref, Yabs, "Y")
+    got = tj.outctl_bwd(dev_bf16(dYb), Xq, Wq, args[2], args[3], 4, 1, out_dtype)
+    ref = oracle.outctl_bwd(dYb, oXq, oWq, Xh, Wh, 4, 1)
+    torch.cuda.synchronize()
+    for name, g in zip(("dX_lo", "dX_hp", "dW_lo", "dW_hp"), got):
+        check(g, *ref[name], name)
