@@ -392,7 +392,7 @@ def cpu_baseline(wl, np, workload):
     flops = 0.0
     names = []
     dt = 0.0
-    budget = 1.2e11                                    # flops of the whole sample: roughly 10-20 s of CPU work
+    budget = 5e11                                      # flops of the whole sample: roughly 10-20 s of CPU work
     lin = wl.config_linears(workload)
     for name, N, D, C, seed, kind in lin:
         n = N

@@ -332,14 +332,9 @@ __global__ __launch_bounds__(kThreads) void quant_dual_kernel(ColArgs a)
     const int64_t R = a.R, C = a.C;
     const uint32_t tiles_r = (uint32_t)((R + kTileR - 1) / kTileR);
     const uint32_t gx = (uint32_t)((C + kTileC - 1) / kTileC);              // column tiles
-    // Workgroup ids are dealt round-robin over the 8 XCDs; each XCD takes a contiguous run of tiles (column tile fastest),
-    // so the pieces of an output cache line that neighbouring tiles write (32 bytes of row codes, 4 of row scales, 8 of
-    // column scales per tile) meet in one L2 and leave it as whole lines
-    uint32_t lin = lin0;
-    {
-        const uint32_t per_xcd = gridDim.x / 8;
-        if (lin < per_xcd * 8) lin = (lin & 7) * per_xcd + (lin >> 3);
-    }
+    // (dealing the tiles to the XCDs in contiguous bands, as the strip kernel does, was measured here: 8 % fewer bytes
+    // written, but 65 us against 58.7 on 8192 x 8192)
+    const uint32_t lin = lin0;
     // workgroup-uniform: keep them (and everything derived from them) in scalar registers
     const uint32_t by = __builtin_amdgcn_readfirstlane(lin / gx), bx = __builtin_amdgcn_readfirstlane(lin % gx);
     const int64_t C0 = (int64_t)bx * kTileC;
