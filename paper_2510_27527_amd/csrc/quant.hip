@@ -527,17 +527,18 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
         uint32_t w[16];                                            // bf16 pairs, or bytes of two codes
         uint32_t sb[PACKED ? 16 : 1];                              // packed: scale bytes
     };
-    // packed source with 1 x 128 outer blocks: the strip lies inside one block column, so each of its 128 rows has one
-    // outer scale; the wave keeps them in its own corner of LDS
+    // packed source: the outer scale of each of the strip's 128 rows, in the wave's own corner of LDS (1 x 128 outer
+    // blocks: the strip lies inside one block column, so a row has one; per-tensor scale: 128 copies of it, so that the
+    // decode is the same code for both)
     __shared__ float row_sg_all[PACKED ? kThreads / 64 : 1][PACKED ? kStripR : 1];
     float *row_sg = row_sg_all[PACKED ? wave : 0];
-    const bool src_blocks = PACKED && a.src_outer != 0;
-    if (src_blocks && have) {
+    if (PACKED && have) {
+        const bool src_blocks = a.src_outer != 0;
         const int64_t nbc = C >> 7;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int64_t row = R0 + lane + 64 * h;
-            row_sg[lane + 64 * h] = row < R ? a.src_gscale[row * nbc + tc] : 0.0f;
+            row_sg[lane + 64 * h] = !src_blocks ? src_sg_tensor : row < R ? a.src_gscale[row * nbc + tc] : 0.0f;
         }
         // same wave writes and reads: the compiler's wait on the LDS counter orders them
     }
@@ -584,10 +585,11 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
             m0 = m1 = 0.0f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float sg = src_blocks ? row_sg[16 * s + i] : src_sg_tensor;
+                const float sg = row_sg[16 * s + i];
                 uint32_t cb = r.w[i];
                 if (RHT) cb ^= flips(i) ? 0x88u : 0u;               // the sign bits of the two codes
-                const float2_t pv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cb, 1.0f, 0) * e4m3_value(r.sb[i]);   // exact
+                // P * S_block, exact: the conversion supplies P * 2^120, the scale byte shifted into place is S_block * 2^-120
+                const float2_t pv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cb, 0x1p120f, 0) * u2f(r.sb[i] << 20);
                 x0[i] = pv.x * sg;                                  // the binary32 dequantized value: one rounding
                 x1[i] = pv.y * sg;
                 m0 = fmaxf(m0, fabsf(x0[i]));
@@ -606,15 +608,16 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
         }
     };
 
-    Raw cur, nxt;
+    Raw raw[2];                                                    // slab s lives in raw[s % 2] (s is a constant after unrolling)
     if (OUTER == 1 && have) {
         // first pass: the maximum of each column over the strip's 128 rows = one outer block of the output row
         float cm0 = 0.0f, cm1 = 0.0f;
-        fetch(std::false_type{}, 0, cur);
+        fetch(std::false_type{}, 0, raw[0]);
 #pragma unroll
         for (int s = 0; s < kSlabs; ++s) {
             if (s >= nslab) break;
-            if (s + 1 < nslab) fetch(std::false_type{}, s + 1, nxt);
+            const Raw &cur = raw[s & 1];
+            if (s + 1 < nslab) fetch(std::false_type{}, s + 1, raw[(s + 1) & 1]);
             if constexpr (!PACKED && !RHT) {
                 ushort2_t m2 = {0, 0};
 #pragma unroll
@@ -627,7 +630,6 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
                 cm0 = fmaxf(cm0, m0);
                 cm1 = fmaxf(cm1, m1);
             }
-            cur = nxt;
         }
         os[0] = outer_scale(cm0);
         os[1] = outer_scale(cm1);
@@ -645,11 +647,12 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
     __shared__ __attribute__((aligned(16))) uint8_t sc_stage[kStripC * kScPitch];
     uint32_t scb[2][2] = {{0, 0}, {0, 0}};                          // scale bytes of slabs 0..3 and 4..7, per column
     const bool wide = (int)wave < nwide;
-    if (have) fetch(std::true_type{}, 0, cur);
+    if (have) fetch(std::true_type{}, 0, raw[0]);
 #pragma unroll
     for (int s = 0; s < kSlabs; ++s) {
         if (s >= nslab) break;
-        if (s + 1 < nslab) fetch(std::true_type{}, s + 1, nxt);
+        const Raw &cur = raw[s & 1];
+        if (s + 1 < nslab) fetch(std::true_type{}, s + 1, raw[(s + 1) & 1]);
         float x0[16], x1[16], mx[2];
         decode(cur, s, x0, x1, mx[0], mx[1]);
 #pragma unroll
@@ -672,7 +675,6 @@ __global__ __launch_bounds__(kThreads) void quant_colw_kernel(ColArgs a0, ColArg
                 a.k.scales[e >> 4] = (uint8_t)sc;
             }
         }
-        cur = nxt;
     }
     if (nwide == 0) return;                                         // uniform over the workgroup
     if (wide) {
