@@ -79,6 +79,8 @@ def lib():
         L.oracle_osci_update.argtypes = [p, p, p, p, i64, i64, i32]
         L.oracle_osci_suppress.restype = i64
         L.oracle_osci_suppress.argtypes = [p, p, p, f32, i64, i64]
+        L.oracle_osci_scores.restype = i32
+        L.oracle_osci_scores.argtypes = [p, i64, i64, p, p]
         L.oracle_dequant_f32.restype = i32
         L.oracle_dequant_f32.argtypes = [p, p, p, i64, i64, i32, p]
         L.oracle_dequant_f64.restype = i32
@@ -294,6 +296,49 @@ def osci_suppress(W, dist_m, dist_q, tau: float) -> int:
     if n < 0:
         raise ValueError("oracle_osci_suppress: bad shape")
     return int(n)
+
+
+def osci_scores(W):
+    """Appendix Alg. 3: (Q(W), sensitivity score |W - Q(W)| / binwidth(Q(W))) of every element, binary32."""
+    assert W.dtype == np.float32 and W.flags.c_contiguous and W.ndim == 2
+    q, s = np.empty_like(W), np.empty_like(W)
+    if lib().oracle_osci_scores(_ptr(W), W.shape[0], W.shape[1], _ptr(q), _ptr(s)) != 0:
+        raise ValueError("oracle_osci_scores: bad shape")
+    return q, s
+
+
+def osci_select(W, k: int):
+    """Appendix Alg. 3 at the first step of a period: the k elements with the largest sensitivity scores (equal scores in
+    ascending index order), as an ascending list of flat indices, with the states of the tracked subset:
+    (idx u32 [k], master snapshot, quantized snapshot, dist_M = 0, dist_Q = 0)."""
+    q, s = osci_scores(W)
+    order = np.argsort(-s.reshape(-1), kind="stable")[:k]         # stable: equal scores keep ascending index order
+    idx = np.sort(order).astype(np.uint32)
+    z = np.zeros(k, np.float32)
+    return idx, W.reshape(-1)[idx].copy(), q.reshape(-1)[idx].copy(), z, z.copy()
+
+
+def osci_update_sparse(W, idx, W_prev_s, Q_prev_s, dist_m_s, dist_q_s) -> None:
+    """Appendix Alg. 3 at a later step, in place on the four subset states: the distances grow by the moves of the
+    tracked master weights and of their quantized values, then the snapshots are replaced."""
+    q = quant_dequant_weight(W).reshape(-1)[idx]
+    w = W.reshape(-1)[idx]
+    dist_m_s += np.abs(w - W_prev_s)                              # binary32 throughout: one rounding per operation
+    dist_q_s += np.abs(q - Q_prev_s)
+    W_prev_s[:] = w
+    Q_prev_s[:] = q
+
+
+def osci_suppress_sparse(W, idx, dist_m_s, dist_q_s, tau: float) -> int:
+    """Alg. 1 on the tracked subset, in place on W: a tracked element whose risk dist_Q / dist_M reaches tau is reset to
+    Q(W) at that element; returns the number of resets."""
+    q = quant_dequant_weight(W).reshape(-1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        risk = dist_q_s / dist_m_s                                # binary32 quotient; 0 / 0 is NaN and compares false
+        hit = risk >= np.float32(tau)
+    flat = W.reshape(-1)
+    flat[idx[hit]] = q[idx[hit]]
+    return int(hit.sum())
 
 
 # ----- OutControl split linear (Sec. 4.2) -------------------------------------------------------

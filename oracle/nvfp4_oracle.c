@@ -68,6 +68,15 @@
  *       accumulate in binary32, one rounding per operation; the risk is the
  *       binary32 quotient dist_Q / dist_M (0 / 0 compares false: an element that
  *       never moved is not reset).
+ *   R14 Memory-efficient OsciReset statistics (Appendix Alg. 3): the sensitivity
+ *       score of a weight is s = |w - Q(w)| / binwidth(Q(w)) in binary32, one
+ *       rounding per operation, with binwidth = b(code) * RN(S_b * S_g) and b the
+ *       length of the interval of scaled values that round to the code's
+ *       magnitude: 0.5 for 0, 0.5, 1 and 1.5; 0.75 for 2 (1.75 .. 2.5); 1 for 3;
+ *       1.5 for 4 (3.5 .. 5); 1 for 6 (5 .. 6, nothing lies beyond the block
+ *       maximum).  A block with scale 0 scores 0.  "Top p %" is the k elements
+ *       with the largest scores, k given by the caller; equal scores are taken in
+ *       ascending index order; the index list is kept in ascending order.
  *
  * Parity status: R1, R6, R7, R12 (which bits, which summation order) are not fixed by the paper ("parity unpinned" by
  * the paper itself); they are pinned by the property tests in tests/ (grid
@@ -471,6 +480,37 @@ int64_t oracle_osci_suppress(float *W, const float *dist_m, const float *dist_q,
     }
     free(q);
     return count;
+}
+
+/* Appendix Alg. 3, first step of a period: Q(W) and the sensitivity score of every element (R14).  Either output may
+ * be NULL.  Selection of the top k scores and the gathers are left to the caller (plain array operations). */
+int oracle_osci_scores(const float *W, int64_t rows, int64_t K, float *q_out, float *score)
+{
+    static const float bin[8] = {0.5f, 0.5f, 0.5f, 0.5f, 0.75f, 1.0f, 1.5f, 1.0f};
+    if (rows < 0 || K < 0 || K % 128) return -1;
+    uint8_t *codes = (uint8_t *)calloc((size_t)(rows * K / 2) + 1, 1);
+    uint8_t *scales = (uint8_t *)calloc((size_t)(rows * K / 16) + 1, 1);
+    float *gs = (float *)calloc((size_t)(rows * (K / 128)) + 1, sizeof(float));
+    float *q = (float *)malloc(sizeof(float) * (size_t)(rows * K + 1));
+    int rc = quantize_rows_impl(W, rows, K, ROUND_RTN, SCALE_NE, OUTER_BLOCK128, 0, 0, codes, scales, gs, NULL, NULL, 0, NULL);
+    if (rc == 0) rc = oracle_dequant_f32(codes, scales, gs, rows, K, OUTER_BLOCK128, q);
+    if (rc == 0)
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t k = 0; k < K; ++k) {
+                const int64_t i = r * K + k;
+                uint8_t byte = codes[r * (K / 2) + k / 2];
+                uint8_t nib = (k & 1) ? (byte >> 4) : (byte & 0xF);
+                float S_b = oracle_e4m3_value(scales[r * (K / 16) + k / 16]);
+                float S_g = gs[r * (K / 128) + k / 128];
+                volatile float unit = S_b * S_g;
+                volatile float width = bin[nib & 7] * unit;
+                volatile float num = fabsf(W[i] - q[i]);
+                volatile float sc = width == 0.0f ? 0.0f : num / width;
+                if (score) score[i] = sc;
+                if (q_out) q_out[i] = q[i];
+            }
+    free(codes); free(scales); free(gs); free(q);
+    return rc;
 }
 
 /* ------------------------------------------------------------------ GEMM -- */

@@ -103,3 +103,105 @@ def test_bad_shapes():
     W = np.zeros((2, 64), np.float32)
     with pytest.raises(ValueError):
         oracle.quant_dequant_weight(W)                  # K % 128
+
+
+# ---- memory-efficient statistics (Appendix Alg. 3) ----------------------------------------------------------------
+
+def test_sensitivity_score_by_hand_in_every_bin():
+    """In the groups of base_matrix the scale is 1 (or 448), so the score can be worked out by hand from the FP4 grid:
+    |w - nearest value| over the length of the interval that rounds to that value (0.5 up to 1.5; 1.75..2.5 for 2;
+    2.5..3.5 for 3; 3.5..5 for 4; 5..6 for 6)."""
+    W = base_matrix()
+    cases = [(0.1, 0.1 / 0.5), (0.3, 0.2 / 0.5), (1.1, 0.1 / 0.5), (1.6, 0.1 / 0.5), (2.2, 0.2 / 0.75), (1.8, 0.2 / 0.75),
+             (3.4, 0.4 / 1.0), (2.6, 0.4 / 1.0), (4.9, 0.9 / 1.5), (3.6, 0.4 / 1.5), (5.2, 0.8 / 1.0), (-2.2, 0.2 / 0.75),
+             (6.0, 0.0), (0.0, 0.0), (0.25, 0.5), (0.75, 0.5)]                 # the last two sit on a rounding threshold
+    pos = [(1, 16 * (1 + g % 7) + 1 + g // 7) for g in range(len(cases))]
+    for p, (w, _) in zip(pos, cases):
+        W[p] = w
+    W[3, 1] = 448 * 1.1                                                        # group scaled by 448: same score as 1.1
+    q, s = oracle.osci_scores(W)
+    assert np.array_equal(q, oracle.quant_dequant_weight(W))
+    for p, (w, want) in zip(pos, cases):
+        assert abs(float(s[p]) - want) < 2e-6, (w, float(s[p]), want)
+    assert abs(float(s[3, 1]) - 0.2) < 2e-6
+    assert s[0, 0] == 0 and np.all(s >= 0) and np.all(s <= 0.8 + 1e-6)
+    # an all-zero outer block: scale 1 by convention, everything scores 0
+    Z = np.zeros((1, 128), np.float32)
+    assert not oracle.osci_scores(Z)[1].any()
+
+
+def test_selection_takes_the_largest_scores_and_equal_scores_in_index_order():
+    W = base_matrix(rows=2, K=256)
+    # scores (scale 1): 0.4 at three places, 0.2 at two, 0.5 once
+    W[0, 17], W[0, 40], W[1, 150] = 0.3, 1.3, 0.7           # |.|: 0.2 / 0.5 = 0.4 each
+    W[0, 20], W[1, 21] = 1.1, 0.6                            # 0.2
+    W[1, 100] = 0.25                                         # 0.5: on the threshold
+    flat = lambda r, c: r * 256 + c
+    idx, wm, wq, dm, dq = oracle.osci_select(W, 3)
+    assert idx.dtype == np.uint32 and list(idx) == [flat(0, 17), flat(0, 40), flat(1, 100)]      # 0.5, then the two first 0.4
+    assert list(wm) == [np.float32(0.3), np.float32(1.3), np.float32(0.25)] and list(wq) == [0.5, 1.5, 0.0]
+    assert not dm.any() and not dq.any()
+    idx4 = oracle.osci_select(W, 4)[0]
+    assert list(idx4) == [flat(0, 17), flat(0, 40), flat(1, 100), flat(1, 150)]
+    idx6 = oracle.osci_select(W, 6)[0]
+    assert list(idx6) == sorted([flat(0, 17), flat(0, 40), flat(1, 100), flat(1, 150), flat(0, 20), flat(1, 21)])
+    assert len(oracle.osci_select(W, 0)[0]) == 0
+    # property on random weights: nothing outside the selection scores higher than anything inside
+    rng = np.random.default_rng(3)
+    R = (rng.standard_normal((8, 384)) * 0.02).astype(np.float32)
+    s = oracle.osci_scores(R)[1].reshape(-1)
+    k = 150
+    sel = oracle.osci_select(R, k)[0]
+    assert len(sel) == k and np.all(np.diff(sel.astype(np.int64)) > 0)
+    mask = np.zeros(R.size, bool)
+    mask[sel] = True
+    assert s[mask].min() >= s[~mask].max()
+
+
+def test_tracking_every_element_is_the_dense_algorithm():
+    """With every element selected, Alg. 3 is Alg. 2, and the reset on the subset is Alg. 1: same states bit for bit
+    over a period of random walks (the pin of the dense functions therefore carries over)."""
+    rng = np.random.default_rng(11)
+    W = (rng.standard_normal((6, 256)) * 0.02).astype(np.float32)
+    Wd = W.copy()
+    Wp, dm, dq = np.empty_like(W), np.empty_like(W), np.empty_like(W)
+    oracle.osci_update(Wd, Wp, dm, dq, 0)
+    idx, wm, wq, sm, sq = oracle.osci_select(W, W.size)
+    assert np.array_equal(idx, np.arange(W.size))
+    for t in range(1, 7):
+        step = (rng.standard_normal(W.shape) * 2e-3).astype(np.float32) * (rng.random(W.shape) < 0.5)
+        W += step
+        Wd += step
+        oracle.osci_update(Wd, Wp, dm, dq, t)
+        oracle.osci_update_sparse(W, idx, wm, wq, sm, sq)
+        assert np.array_equal(sm, dm.reshape(-1)) and np.array_equal(sq, dq.reshape(-1))
+        assert np.array_equal(wm, Wp.reshape(-1)) and np.array_equal(wq, oracle.quant_dequant_weight(Wp).reshape(-1))
+    n_dense = oracle.osci_suppress(Wd, dm, dq, TAU)
+    n_sparse = oracle.osci_suppress_sparse(W, idx, sm, sq, TAU)
+    assert n_dense == n_sparse > 0 and np.array_equal(W, Wd)
+
+
+def test_subset_tracks_the_oscillating_element_of_the_hand_made_trajectory():
+    """The element hopping 0.24 <-> 0.26 sits next to a threshold (score 0.48): it is in a 5 % selection, is reset after
+    the period, and nothing outside the selection is touched."""
+    W = base_matrix()
+    rng = np.random.default_rng(5)
+    free = np.ones(W.shape, bool)
+    free[:, 0::16] = False
+    W[free] = (np.round(rng.uniform(0, 6, free.sum()) * 2) / 2).astype(np.float32)       # bin centres and thresholds mixed
+    W[free] = np.where(np.isin(W[free], [0, .5, 1, 1.5, 2, 3, 4, 6]), W[free], 3.0)      # keep bin centres only: score 0
+    osc = (2, 17)
+    W[osc] = 0.24
+    k = max(1, W.size // 20)
+    idx, wm, wq, sm, sq = oracle.osci_select(W, k)
+    j = int(np.searchsorted(idx, osc[0] * W.shape[1] + osc[1]))
+    assert idx[j] == osc[0] * W.shape[1] + osc[1]
+    before = W.copy()
+    for t in range(1, 11):
+        W[osc] = 0.26 if t % 2 else 0.24
+        oracle.osci_update_sparse(W, idx, wm, wq, sm, sq)
+    assert sq[j] == 5.0 and abs(sm[j] - 0.2) < 1e-5
+    assert oracle.osci_suppress_sparse(W, idx, sm, sq, TAU) == 1
+    assert W[osc] == 0.0                                    # 0.24 rounds to the value 0: the centre of its bin
+    W[osc] = before[osc]
+    assert np.array_equal(W, before)
