@@ -346,6 +346,22 @@ def osci_lines(tj, torch, dev):
     gbs = 16.0 * n * n / (ms * 1e-3) / 1e9         # reads of W, dist_M, dist_Q, and (worst case, as here: nearly every
                                                     # weight is over the threshold) W written back
     res["osci_suppress_8192x8192"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    # memory-efficient statistics (Appendix Alg. 3) on the 5 % of the weights closest to a rounding threshold: the
+    # selection reads W five times (three radix digits, count, emit); a later step reads W once (4 B per weight) and
+    # moves 36 B per tracked weight
+    del Wp, dm, dq
+    k = n * n // 20
+    st = tj.osci_select(W, k)
+    torch.cuda.synchronize()
+    ms = time_events(torch, lambda i: tj.osci_select(W, k), 5)
+    res["osci_select_top5pct_8192x8192"] = {"ms": round(ms, 4), "GB/s": round(5 * 4.0 * n * n / (ms * 1e-3) / 1e9, 1)}
+    fn = lambda i: tj.osci_update_sparse(W2 if i % 2 == 0 else W, *st)
+    for i in range(5):
+        fn(i)
+    torch.cuda.synchronize()
+    ms = time_events(torch, fn, 20)
+    gbs = (4.0 * n * n + 36.0 * k) / (ms * 1e-3) / 1e9
+    res["osci_update_top5pct_8192x8192"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
     return res
 
 

@@ -243,6 +243,32 @@ int nvfp4_osci_suppress(float *W, const float *dist_m, const float *dist_q, floa
                         unsigned long long *n_reset, void *stream);
 
 /*
+ * The memory-efficient statistics of Appendix Alg. 3: only the k weights closest to a rounding threshold are tracked
+ * (the paper tracks the top 5 % of the sensitivity score s = |W - Q(W)| / binwidth(Q(W)); the caller passes
+ * k = ceil(p * C * D)).  binwidth = (length of the interval of scaled values that round to the element's FP4 magnitude:
+ * 0.5 for 0 .. 1.5, 0.75 for 2, 1 for 3, 1.5 for 4, 1 for 6) * S_block * S_global; equal scores are taken in ascending
+ * index order.  State of the subset, all device arrays of k entries owned by the caller: idx (flat indices into W,
+ * ascending), W_prev_s / Q_prev_s (master / quantized snapshots), dist_m_s / dist_q_s.  C * D <= 2^31, D % 128 == 0,
+ * W 16-byte aligned.
+ *
+ * nvfp4_osci_select - first step of a period (t0 = 0): finds the k largest scores, writes idx, the two snapshots and
+ *   zero distances.  ws: nvfp4_osci_select_workspace_bytes(C, D) bytes, 16-byte aligned.  Ten launches, five reads of W.
+ * nvfp4_osci_update_sparse - a later step: dist_m_s += |W[idx] - W_prev_s|, dist_q_s += |Q(W)[idx] - Q_prev_s|, then
+ *   the snapshots are replaced.
+ * nvfp4_osci_suppress_sparse - Alg. 1 on the subset: W[idx[j]] = Q(W)[idx[j]] where dist_q_s[j] / dist_m_s[j] >= tau;
+ *   n_reset as in nvfp4_osci_suppress.
+ * With k = C * D the three calls compute exactly what nvfp4_osci_update / nvfp4_osci_suppress compute.
+ * Errors: NULL, SHAPE (also k < 0, k > C * D, C * D > 2^31), ENUM (tau <= 0), ALIGN, WORKSPACE.
+ */
+size_t nvfp4_osci_select_workspace_bytes(int64_t C, int64_t D);
+int nvfp4_osci_select(const float *W, int64_t C, int64_t D, int64_t k, uint32_t *idx, float *W_prev_s, float *Q_prev_s,
+                      float *dist_m_s, float *dist_q_s, void *ws, size_t ws_bytes, void *stream);
+int nvfp4_osci_update_sparse(const float *W, int64_t C, int64_t D, const uint32_t *idx, int64_t k, float *W_prev_s,
+                             float *Q_prev_s, float *dist_m_s, float *dist_q_s, void *stream);
+int nvfp4_osci_suppress_sparse(float *W, int64_t C, int64_t D, const uint32_t *idx, int64_t k, const float *dist_m_s,
+                               const float *dist_q_s, float tau, unsigned long long *n_reset, void *stream);
+
+/*
  * Scratch bytes an operation needs.  op = NVFP4_OP_*.  QUANTIZE: (N, D) = (R, C) of the source, C ignored.
  * GEMM: Out is [N x C] with reduction length D.  LINEAR_*: as in the calls above.  Returns 0 for a bad op.
  */

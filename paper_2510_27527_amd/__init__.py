@@ -7,4 +7,4 @@ its HIP sources (``csrc/``), the build step (``build.py``) and a thin ctypes bin
 from . import binding  # noqa: F401
 from .binding import (NVFP4Error, NVFP4Tensor, alloc_nvfp4, alloc_workspace, amax_bf16, gemm_nt, gemm_nt_static,  # noqa: F401
                       linear_bwd_dw,
-                      linear_bwd, linear_bwd_dx, linear_fwd, osci_suppress, osci_update, outctl_bwd, outctl_fwd, quantize, quantize_dual, stream_key, workspace_bytes)
+                      linear_bwd, linear_bwd_dx, linear_fwd, osci_select, osci_suppress, osci_suppress_sparse, osci_update, osci_update_sparse, outctl_bwd, outctl_fwd, quantize, quantize_dual, stream_key, workspace_bytes)

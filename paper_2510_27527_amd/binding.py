@@ -24,7 +24,7 @@ SRC_BF16, SRC_NVFP4 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 OP_QUANTIZE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD_DX, OP_LINEAR_BWD_DW, OP_LINEAR_BWD = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_gemm_nt_static", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd", "nvfp4_osci_update", "nvfp4_osci_suppress", "nvfp4_outctl_fwd", "nvfp4_outctl_bwd", "nvfp4_outctl_workspace_bytes",
+EXPORTS = ["nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm_nt", "nvfp4_gemm_nt_static", "nvfp4_linear_fwd", "nvfp4_linear_bwd_dx", "nvfp4_linear_bwd_dw", "nvfp4_linear_bwd", "nvfp4_osci_update", "nvfp4_osci_suppress", "nvfp4_osci_select", "nvfp4_osci_update_sparse", "nvfp4_osci_suppress_sparse", "nvfp4_osci_select_workspace_bytes", "nvfp4_outctl_fwd", "nvfp4_outctl_bwd", "nvfp4_outctl_workspace_bytes",
            "nvfp4_workspace_bytes", "nvfp4_gemm_plan", "nvfp4_amax_bf16", "nvfp4_stream_key", "nvfp4_strerror", "nvfp4_version"]
 
 
@@ -87,6 +87,14 @@ def lib():
         L.nvfp4_osci_update.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
         L.nvfp4_osci_suppress.restype = i32
         L.nvfp4_osci_suppress.argtypes = [vp, vp, vp, C.c_float, i64, i64, vp, vp]
+        L.nvfp4_osci_select_workspace_bytes.restype = C.c_size_t
+        L.nvfp4_osci_select_workspace_bytes.argtypes = [i64, i64]
+        L.nvfp4_osci_select.restype = i32
+        L.nvfp4_osci_select.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.nvfp4_osci_update_sparse.restype = i32
+        L.nvfp4_osci_update_sparse.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp, vp]
+        L.nvfp4_osci_suppress_sparse.restype = i32
+        L.nvfp4_osci_suppress_sparse.argtypes = [vp, i64, i64, vp, i64, vp, vp, C.c_float, vp, vp]
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
         L.nvfp4_gemm_plan.restype = i32
@@ -366,6 +374,46 @@ def osci_suppress(W: torch.Tensor, dist_m: torch.Tensor, dist_q: torch.Tensor, t
         assert n_reset.dtype == torch.int64 and n_reset.numel() == 1 and n_reset.is_cuda
     _check(lib().nvfp4_osci_suppress(_ptr(W), _ptr(dist_m), _ptr(dist_q), tau, Cc, D, _ptr(n_reset), _stream()),
            "nvfp4_osci_suppress")
+
+
+def _check_subset(k: int, idx, *states):
+    assert idx.dtype == torch.int32 and idx.numel() == k and idx.is_contiguous() and idx.is_cuda, "idx"
+    for t in states:
+        assert t.dtype == torch.float32 and t.numel() == k and t.is_contiguous() and t.is_cuda, "subset state"
+
+
+def osci_select(W: torch.Tensor, k: int):
+    """nvfp4_osci_select (Appendix Alg. 3, first step of a period): returns (idx, W_prev_s, Q_prev_s, dist_m_s, dist_q_s)
+    of the k weights with the largest sensitivity scores; idx holds 32-bit flat indices (int32 storage, read as unsigned)."""
+    Cc, D = W.shape
+    _check_f32(W, (Cc, D), "W")
+    idx = torch.empty(k, dtype=torch.int32, device=W.device)
+    st = [torch.empty(k, dtype=torch.float32, device=W.device) for _ in range(4)]
+    nbytes = lib().nvfp4_osci_select_workspace_bytes(Cc, D)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    _check(lib().nvfp4_osci_select(_ptr(W), Cc, D, k, _ptr(idx), *[_ptr(t) for t in st], _ptr(ws), ws.numel(), _stream()),
+           "nvfp4_osci_select")
+    return (idx, *st)
+
+
+def osci_update_sparse(W, idx, W_prev_s, Q_prev_s, dist_m_s, dist_q_s):
+    """nvfp4_osci_update_sparse: a later step of the period, in place on the four subset states."""
+    Cc, D = W.shape
+    _check_f32(W, (Cc, D), "W")
+    _check_subset(idx.numel(), idx, W_prev_s, Q_prev_s, dist_m_s, dist_q_s)
+    _check(lib().nvfp4_osci_update_sparse(_ptr(W), Cc, D, _ptr(idx), idx.numel(), _ptr(W_prev_s), _ptr(Q_prev_s), _ptr(dist_m_s),
+                                          _ptr(dist_q_s), _stream()), "nvfp4_osci_update_sparse")
+
+
+def osci_suppress_sparse(W, idx, dist_m_s, dist_q_s, tau: float, n_reset: Optional[torch.Tensor] = None):
+    """nvfp4_osci_suppress_sparse: reset the oscillating tracked elements of W in place."""
+    Cc, D = W.shape
+    _check_f32(W, (Cc, D), "W")
+    _check_subset(idx.numel(), idx, dist_m_s, dist_q_s)
+    if n_reset is not None:
+        assert n_reset.dtype == torch.int64 and n_reset.numel() == 1 and n_reset.is_cuda
+    _check(lib().nvfp4_osci_suppress_sparse(_ptr(W), Cc, D, _ptr(idx), idx.numel(), _ptr(dist_m_s), _ptr(dist_q_s), tau,
+                                            _ptr(n_reset), _stream()), "nvfp4_osci_suppress_sparse")
 
 
 def outctl_fwd(X_lo, W_lo, X_hp, W_hp, out_dtype: int = OUT_BF16, *, outer: int = OUTER_TENSOR, Y=None, Xq=None, Wq=None, ws=None):

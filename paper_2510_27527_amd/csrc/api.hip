@@ -633,6 +633,58 @@ int nvfp4_osci_suppress(float *W, const float *dist_m, const float *dist_q, floa
                ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
+// the tracked subset of Appendix Alg. 3: 32-bit indices, so at most 2^31 weights per matrix
+static int check_osci_sparse(const void *W, int64_t C, int64_t D, const void *idx, int64_t k, const void *a, const void *b)
+{
+    if (!W) return NVFP4_ERR_NULL;
+    if (C < 0 || D < 0 || D % 128 != 0 || k < 0) return NVFP4_ERR_SHAPE;
+    if (C > 0 && D > ((int64_t)1 << 31) / C) return NVFP4_ERR_SHAPE;
+    if (k > C * D) return NVFP4_ERR_SHAPE;
+    if (k > 0 && (!idx || !a || !b)) return NVFP4_ERR_NULL;
+    if (!aligned16(W)) return NVFP4_ERR_ALIGN;
+    return NVFP4_OK;
+}
+
+size_t nvfp4_osci_select_workspace_bytes(int64_t C, int64_t D)
+{
+    if (C < 0 || D < 0 || (C > 0 && D > ((int64_t)1 << 31) / C)) return 0;
+    return osci_select_workspace_bytes(C * D);
+}
+
+int nvfp4_osci_select(const float *W, int64_t C, int64_t D, int64_t k, uint32_t *idx, float *W_prev_s, float *Q_prev_s,
+                      float *dist_m_s, float *dist_q_s, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_osci_sparse(W, C, D, idx, k, W_prev_s, Q_prev_s);
+    if (rc) return rc;
+    if (k > 0 && (!dist_m_s || !dist_q_s)) return NVFP4_ERR_NULL;
+    if (k == 0 || C * D == 0) return NVFP4_OK;
+    if (!ws || ws_bytes < osci_select_workspace_bytes(C * D)) return NVFP4_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) & 15u) return NVFP4_ERR_ALIGN;
+    return launch_osci_select(W, C * D, k, idx, W_prev_s, Q_prev_s, dist_m_s, dist_q_s, ws, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_osci_update_sparse(const float *W, int64_t C, int64_t D, const uint32_t *idx, int64_t k, float *W_prev_s,
+                             float *Q_prev_s, float *dist_m_s, float *dist_q_s, void *stream)
+{
+    int rc = check_osci_sparse(W, C, D, idx, k, W_prev_s, Q_prev_s);
+    if (rc) return rc;
+    if (k > 0 && (!dist_m_s || !dist_q_s)) return NVFP4_ERR_NULL;
+    return launch_osci_update_sparse(W, C * D, idx, k, W_prev_s, Q_prev_s, dist_m_s, dist_q_s, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_osci_suppress_sparse(float *W, int64_t C, int64_t D, const uint32_t *idx, int64_t k, const float *dist_m_s,
+                               const float *dist_q_s, float tau, unsigned long long *n_reset, void *stream)
+{
+    int rc = check_osci_sparse(W, C, D, idx, k, dist_m_s, dist_q_s);
+    if (rc) return rc;
+    if (!(tau > 0.0f)) return NVFP4_ERR_ENUM;
+    if (n_reset && (reinterpret_cast<uintptr_t>(n_reset) & 7u)) return NVFP4_ERR_ALIGN;
+    return launch_osci_suppress_sparse(W, C * D, idx, k, dist_m_s, dist_q_s, tau, n_reset, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
 int nvfp4_linear_fwd(const void *X, const void *W, int64_t N, int64_t D, int64_t C, void *Y, int out_dtype,
                      nvfp4_tensor *Xq_ctx, nvfp4_tensor *Wq_ctx, int outer_mode, void *ws, size_t ws_bytes,
                      void *stream)

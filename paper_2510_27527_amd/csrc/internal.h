@@ -96,6 +96,14 @@ hipError_t launch_transpose_bf16(const void *src, void *dst, int64_t R, int64_t 
 hipError_t launch_osci_update(const float *W, float *W_prev, float *dist_m, float *dist_q, int64_t n, int first, hipStream_t st);
 hipError_t launch_osci_suppress(float *W, const float *dist_m, const float *dist_q, float tau, int64_t n,
                                 unsigned long long *n_reset, hipStream_t st);
+// Appendix Alg. 3 (the k weights closest to a rounding threshold): selection, update and reset on the tracked subset
+size_t osci_select_workspace_bytes(int64_t n);
+hipError_t launch_osci_select(const float *W, int64_t n, int64_t k, uint32_t *idx, float *wp, float *qp, float *dm, float *dq,
+                              void *ws, hipStream_t st);
+hipError_t launch_osci_update_sparse(const float *W, int64_t n, const uint32_t *idx, int64_t k, float *wp, float *qp, float *dm,
+                                     float *dq, hipStream_t st);
+hipError_t launch_osci_suppress_sparse(float *W, int64_t n, const uint32_t *idx, int64_t k, const float *dm, const float *dq,
+                                       float tau, unsigned long long *n_reset, hipStream_t st);
 
 uint64_t stream_key(uint64_t seed, uint32_t tensor_id);
 

@@ -244,6 +244,34 @@ def test_osci_calls_reject_bad_arguments(lib):
     assert sp(n=FAKE + 4) == -5
 
 
+def test_osci_subset_calls_reject_bad_arguments(lib):
+    """Appendix Alg. 3 entry points: every validation path, and the calls that have nothing to do (k = 0, empty matrix)
+    return before any launch"""
+    big = 1 << 40
+    sel = lambda W=FAKE, Cc=4, D=128, k=8, idx=FAKE, a=FAKE, b=FAKE, c=FAKE, d=FAKE, ws=FAKE, wsb=big: lib.nvfp4_osci_select(
+        W, Cc, D, k, idx, a, b, c, d, ws, wsb, None)
+    assert sel(W=None) == -1 and sel(idx=None) == -1 and sel(d=None) == -1
+    assert sel(D=192) == -2 and sel(k=-1) == -2 and sel(k=4 * 128 + 1) == -2 and sel(Cc=1 << 30, D=128) == -2
+    assert sel(wsb=16) == -4 and sel(ws=None) == -4
+    assert sel(ws=FAKE + 4) == -5 and sel(W=FAKE + 4) == -5
+    assert sel(k=0, idx=None, a=None, b=None, c=None, d=None, ws=None, wsb=0) == 0
+    assert sel(Cc=0, k=0, ws=None, wsb=0) == 0
+    need = lib.nvfp4_osci_select_workspace_bytes(8192, 8192)
+    assert need == 256 + 8192 + (8192 * 8192 // 2048) * 8
+    assert lib.nvfp4_osci_select_workspace_bytes(-1, 128) == 0 and lib.nvfp4_osci_select_workspace_bytes(1 << 30, 128) == 0
+    up = lambda W=FAKE, Cc=4, D=128, idx=FAKE, k=8, a=FAKE, b=FAKE, c=FAKE, d=FAKE: lib.nvfp4_osci_update_sparse(
+        W, Cc, D, idx, k, a, b, c, d, None)
+    assert up(W=None) == -1 and up(b=None) == -1 and up(c=None) == -1
+    assert up(D=64) == -2 and up(k=513) == -2
+    assert up(k=0, idx=None) == 0
+    sp = lambda W=FAKE, Cc=4, D=128, idx=FAKE, k=8, a=FAKE, b=FAKE, tau=8.0, n=None: lib.nvfp4_osci_suppress_sparse(
+        W, Cc, D, idx, k, a, b, tau, n, None)
+    assert sp(idx=None) == -1 and sp(a=None) == -1
+    assert sp(tau=-1.0) == -3 and sp(tau=float("nan")) == -3
+    assert sp(n=FAKE + 4) == -5
+    assert sp(k=0, idx=None, a=None, b=None) == 0
+
+
 def test_outctl_calls_reject_bad_arguments(lib):
     X, W = _tensor(128, 128), _tensor(64, 128)
     fwd = lambda Xh=FAKE, D_hp=32, outer=0, wsb=1 << 40, D_lo=128: lib.nvfp4_outctl_fwd(

@@ -80,3 +80,83 @@ def test_empty_and_bad_arguments():
         tj.osci_suppress(w, w.clone(), w.clone(), 0.0)
     assert e.value.code == -3
     torch.cuda.synchronize()
+
+
+# ---- memory-efficient statistics (Appendix Alg. 3) ----------------------------------------------------------------
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("shape,frac", [((16, 128), 0.05), ((300, 1152), 0.05), ((2048, 1024), 0.05), ((300, 1152), 1.0),
+                                        ((17, 128), 0.5), ((64, 256), 1.0 / 16384)])
+def test_tracked_subset_matches_the_oracle(shape, frac):
+    """selection (indices and snapshots), every later step and the reset, bit for bit; 2048 x 1024 spans 1024 tiles of
+    the compaction, 17 x 128 ends in a partial tile, the last case tracks a single element"""
+    import paper_2510_27527_amd as tj
+    steps = 5
+    seq = trajectory(shape, 23 + shape[0], steps)
+    k = max(1, int(np.ceil(frac * seq[0].size)))
+    o = list(oracle.osci_select(seq[0], k))
+    g = list(tj.osci_select(torch.from_numpy(seq[0]).cuda(), k))
+    torch.cuda.synchronize()
+    assert np.array_equal(u32(g[0]), o[0])
+    for a, b in zip(g[1:], o[1:]):
+        assert np.array_equal(bits(a.cpu().numpy()), bits(b))
+    for t in range(1, steps + 1):
+        oracle.osci_update_sparse(seq[t], *o)
+        tj.osci_update_sparse(torch.from_numpy(seq[t]).cuda(), *g)
+        torch.cuda.synchronize()
+        for a, b in zip(g[1:], o[1:]):
+            assert np.array_equal(bits(a.cpu().numpy()), bits(b)), t
+    oW, gW = seq[-1].copy(), torch.from_numpy(seq[-1]).cuda()
+    n = torch.zeros(1, dtype=torch.int64, device="cuda")
+    want = oracle.osci_suppress_sparse(oW, o[0], o[3], o[4], TAU)
+    tj.osci_suppress_sparse(gW, g[0], g[3], g[4], TAU, n)
+    torch.cuda.synchronize()
+    assert int(n.item()) == want
+    assert np.array_equal(bits(gW.cpu().numpy()), bits(oW))
+    if frac == 0.05 and shape[0] >= 300:
+        assert want > 0                                 # the hopping elements sit next to thresholds: they are tracked
+
+
+def test_selection_with_many_equal_scores():
+    """weights on a coarse grid give scores with long runs of exact ties, also at the selection threshold: the first
+    ones in index order belong to the subset"""
+    import paper_2510_27527_amd as tj
+    rng = np.random.default_rng(2)
+    W = np.zeros((64, 512), np.float32)
+    W[:, 0::128] = 2688.0
+    W[:, 16::16] = 6.0
+    W[:, 0::128] = 2688.0
+    free = np.ones(W.shape, bool)
+    free[:, 0::16] = False
+    W[free] = rng.choice(np.array([0.0, 0.1, 0.2, 0.6, 1.1, 1.9, 2.2, 3.4, 5.5], np.float32), free.sum())
+    for k in (1, 100, 5000, 20000, W.size):
+        o = oracle.osci_select(W, k)
+        g = tj.osci_select(torch.from_numpy(W).cuda(), k)
+        torch.cuda.synchronize()
+        assert np.array_equal(u32(g[0]), o[0]), k
+        assert np.array_equal(bits(g[2].cpu().numpy()), bits(o[2])), k
+
+
+def test_subset_calls_empty_and_bad_arguments():
+    import paper_2510_27527_amd as tj
+    B = tj.binding
+    w = torch.zeros((4, 128), device="cuda")
+    st = tj.osci_select(w, 0)
+    assert all(t.numel() == 0 for t in st)
+    tj.osci_update_sparse(w, *st)
+    tj.osci_suppress_sparse(w, st[0], st[3], st[4], TAU)
+    z = torch.zeros((0, 128), device="cuda")
+    tj.osci_select(z, 0)
+    with pytest.raises(B.NVFP4Error) as e:
+        tj.osci_select(w, w.numel() + 1)
+    assert e.value.code == -2
+    with pytest.raises(B.NVFP4Error) as e:
+        tj.osci_select(torch.zeros((4, 192), device="cuda"), 1)
+    assert e.value.code == -2
+    st = tj.osci_select(w, 3)
+    with pytest.raises(B.NVFP4Error) as e:
+        tj.osci_suppress_sparse(w, st[0], st[3], st[4], 0.0)
+    assert e.value.code == -3
