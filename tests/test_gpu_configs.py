@@ -22,7 +22,7 @@ import workloads as wl
 pytestmark = pytest.mark.gpu
 
 tj = None
-SAMPLE_ROWS = 48
+SAMPLE_ROWS = 256
 
 
 @pytest.fixture(scope="module", autouse=True)
