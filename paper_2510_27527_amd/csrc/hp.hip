@@ -206,6 +206,34 @@ __global__ __launch_bounds__(kThreads) void transpose_bf16_kernel(const uint16_t
     }
 }
 
+// the same for even R and C, 64 x 128 tile, two elements per access: a wave reads 256 contiguous bytes of a source row and
+// writes 128 contiguous bytes of a destination row
+__global__ __launch_bounds__(kThreads) void transpose_bf16_pairs_kernel(const uint16_t *src, uint16_t *dst, int64_t R, int64_t C,
+                                                                        int tiles_c)
+{
+    __shared__ __attribute__((aligned(4))) uint16_t tile[64][130];
+    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * 64, c0 = (int64_t)(blockIdx.x % tiles_c) * 128;
+    {
+        const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t r = r0 + ty + 4 * i, c = c0 + 2 * tx;
+            if (r < R && c < C) *reinterpret_cast<uint32_t *>(&tile[ty + 4 * i][2 * tx]) = *reinterpret_cast<const uint32_t *>(src + r * C + c);
+        }
+    }
+    __syncthreads();
+    {
+        const int rr = threadIdx.x & 31, cc = threadIdx.x >> 5;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int cl = cc + 8 * i;
+            const int64_t c = c0 + cl, r = r0 + 2 * rr;
+            if (c < C && r < R)
+                *reinterpret_cast<uint32_t *>(dst + c * R + r) = (uint32_t)tile[2 * rr][cl] | ((uint32_t)tile[2 * rr + 1][cl] << 16);
+        }
+    }
+}
+
 }  // namespace
 
 template <int TM, int TN>
@@ -245,6 +273,12 @@ hipError_t launch_hp_gemm_nt(const void *A, const void *B, int64_t M, int64_t N,
 hipError_t launch_transpose_bf16(const void *src, void *dst, int64_t R, int64_t C, hipStream_t st)
 {
     if (R == 0 || C == 0) return hipSuccess;
+    if (R % 2 == 0 && C % 2 == 0) {
+        const int tc = (int)((C + 127) / 128);
+        hipLaunchKernelGGL(transpose_bf16_pairs_kernel, dim3((unsigned)(((R + 63) / 64) * tc)), dim3(kThreads), 0, st,
+                           static_cast<const uint16_t *>(src), static_cast<uint16_t *>(dst), R, C, tc);
+        return hipGetLastError();
+    }
     const int tiles_c = (int)((C + 63) / 64);
     const int64_t tiles = ((R + 63) / 64) * tiles_c;
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)tiles), dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
