@@ -324,7 +324,7 @@ def quantizer_lines(tj, wl, np, torch, dev, warm=300, reps=200):
             a.copy_(b)
         srcs.append(t)
     dsts = [tj.alloc_nvfp4(Cc, R) for _ in range(2)]
-    fn = lambda i: tj.quantize(srcs[i % 8], 1, B.ROUND_SR, dsts[i % 2], seed=7, tensor_id=i)
+    fn = lambda i: tj.quantize(srcs[i % 8], 1, B.ROUND_SR, dsts[i % 2], seed=7, tensor_id=i, ws=ws)
     for i in range(warm):
         fn(i)
     torch.cuda.synchronize()
