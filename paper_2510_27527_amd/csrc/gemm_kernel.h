@@ -75,13 +75,48 @@ __device__ __forceinline__ uint32_t pick(uint4 v, int i) { return i == 0 ? v.x :
 // columns; otherwise lanes run along the columns and accumulator element e sits in row 8 * (e / 4) + 4 * (lane / 32) + e % 4.
 template <int TM, int TN, int OUT, bool SWAP, int OUTER>
 __device__ __forceinline__ void store_tile(float16_t (&acc)[TM][TN], const GemmArgs &g, int64_t m0, int64_t n0, int wm, int wn,
-                                           int lr, int kg)
+                                           int lr, int kg, uint8_t *stage)
 {
     constexpr bool SPLIT = OUT == 2;
     float alpha = 1.0f;
     // tensor mode: both outer scales and the 2^8 of the FP16 pre-scale; block mode: the outer scales are already in
     if (!SPLIT) alpha = OUTER == 0 ? g.a_gscale[0] * g.b_gscale[0] * 256.0f : 256.0f;
-    if (SWAP) {
+    if (SWAP && (g.N & 7) == 0 && m0 + 64 * TM <= g.M && n0 + 64 * TN <= g.N) {
+        // Whole tile, rows 16-byte aligned: a wave's 32 x (32 TN) block of outputs goes through the wave's own corner of
+        // LDS (the pipeline buffers are free by now) and leaves as whole rows - sixteen lanes write one row's 64 TN
+        // contiguous bytes, a store instruction four rows - instead of 16-byte pieces of 32 different rows, which cost
+        // the memory pipeline eight times as many cache-line accesses.  Row pitch 64 TN + 8 bytes: the 8-byte writes
+        // of 32 rows and the 8-byte reads of 2 x 16 pieces both spread over all banks.  Two buffers alternate; the
+        // LDS executes one wave's instructions in order, so neither a barrier nor a wait is needed between a block's
+        // reads and the writes of the block after next.
+        constexpr int PITCH = 64 * TN + 8;
+        uint8_t *outb = reinterpret_cast<uint8_t *>(g.out);
+        const int lane = lr + 32 * kg, wave = wm * 2 + wn;
+        const int piece = lane & 15, rsub = lane >> 4;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            uint8_t *buf = stage + (wave * 2 + (i & 1)) * 32 * PITCH;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bf16x2_t lo = __builtin_convertvector((float2_t){acc[i][j][4 * q] * alpha, acc[i][j][4 * q + 1] * alpha}, bf16x2_t);
+                    const bf16x2_t hi = __builtin_convertvector((float2_t){acc[i][j][4 * q + 2] * alpha, acc[i][j][4 * q + 3] * alpha}, bf16x2_t);
+                    *reinterpret_cast<uint2 *>(buf + lr * PITCH + (j * 32 + 8 * q + 4 * kg) * 2) =
+                        make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+                }
+            const int64_t mrow = m0 + (wm * TM + i) * 32, ncol = n0 + wn * TN * 32;
+            if (piece < 4 * TN) {
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int row = 4 * it + rsub;
+                    const uint2 a = *reinterpret_cast<const uint2 *>(buf + row * PITCH + piece * 16);
+                    const uint2 b = *reinterpret_cast<const uint2 *>(buf + row * PITCH + piece * 16 + 8);
+                    *reinterpret_cast<uint4 *>(outb + ((mrow + row) * g.N + ncol) * 2 + piece * 16) = make_uint4(a.x, a.y, b.x, b.y);
+                }
+            }
+        }
+    } else if (SWAP) {
         // a lane holds one output row (m = lane % 32) and, per 32 x 32 block, four runs of four consecutive columns
         // (n = 8 * (e / 4) + 4 * (lane / 32) + e % 4): each run leaves as one 8-byte store
         uint16_t *outh = reinterpret_cast<uint16_t *>(g.out);
@@ -185,6 +220,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN * (OUTER + 1) >= 8 ? 1 : 2)) voi
     static_assert(LA >= 1 && LB >= 1 && A_SLOTS % kThreads == 0 && B_SLOTS % kThreads == 0, "tile too small");
     static_assert(PS || (LS >= 1 && (ROWS * NC) % kThreads == 0), "per-chunk scale fetch needs whole instructions");
     static_assert(NLOAD <= 15, "vmcnt immediate below assumes at most 15 loads per stage");
+    static_assert(OUT != 0 || 4 * 2 * 32 * (64 * TN + 8) <= 3 * CODE_BYTES, "the bf16 epilogue stages its rows in the code buffers");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
 
@@ -490,10 +526,13 @@ __global__ __launch_bounds__(kThreads, (TM * TN * (OUTER + 1) >= 8 ? 1 : 2)) voi
             }
             buf = nbuf;
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the look-ahead loads before the LDS is released
+        __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the look-ahead loads before the LDS is reused / released
     }
+    // the epilogue stages its output in the pipeline's LDS: every wave's copies have landed and every wave is done
+    // reading fragments
+    if (SWAP) __syncthreads();
 
-    store_tile<TM, TN, OUT, SWAP, OUTER>(acc, g, m0, n0, wm, wn, lr, kg);
+    store_tile<TM, TN, OUT, SWAP, OUTER>(acc, g, m0, n0, wm, wn, lr, kg, smem_raw);
 }
 
 template <int TM, int TN, int OUT, bool PS, int OUTER>
